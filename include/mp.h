@@ -1,0 +1,283 @@
+/*
+ * mp.h - C ABI of the MI355X (gfx950) mixed-precision training-step library.
+ *
+ * The calls are the steps of one mixed-precision training iteration as the
+ * paper states it (Section 3.1: fp16 maths accumulated in fp32, loss scaling,
+ * fp32 master weights; Section 3.2: the optimizer wrapper; Section 3.3:
+ * regularisation on the fp32 copy):
+ *
+ *   forward  : mp_gemm_fwd (+ mp_layernorm_fwd, mp_softmax_fwd, mp_lstm_cell_fwd)
+ *   loss     : mp_mse_scaled | mp_softmax_xent_scaled      (seed gradient x loss scale)
+ *   backward : mp_gemm_bwd_dx, mp_gemm_bwd_dw (+ mp_layernorm_bwd, mp_softmax_bwd,
+ *              mp_lstm_cell_bwd, mp_colsum)
+ *   update   : mp_unscale_check_update   (inspect fp16 gradients, unscale, SGD/Adam on
+ *                                         fp32 masters, rewrite the fp16 copies - or skip)
+ *              mp_loss_scale_update      (halve / count / grow the loss scale)
+ *
+ * Conventions (all entry points):
+ *   - Every pointer marked "device" is GPU memory owned by the caller; the library
+ *     never allocates, frees or retains it.  Pointers marked "host" are read during
+ *     the call only.
+ *   - fp16 data is IEEE binary16 stored as uint16_t bit patterns (mp_half).  Every
+ *     fp32 -> fp16 conversion is round-to-nearest-even and overflows to +-inf (never
+ *     saturates): that overflow is what the loss-scale policy detects.
+ *   - Matrices are row-major with an explicit leading dimension in elements.
+ *   - Every call only enqueues work on `stream` (a hipStream_t passed as void*;
+ *     NULL is the default stream) and returns without synchronising.  The skip
+ *     decision of an overflowing step is taken on the device, so no call depends on
+ *     the host reading device memory; a whole training step can be captured in a HIP
+ *     graph.
+ *   - Return value: MP_OK or a negative error code; mp_last_error() gives a
+ *     thread-local human-readable message for the last failure on this thread.
+ *     A call that returns an error has enqueued nothing.
+ *   - Scratch ("workspace") is caller-provided device memory; each call that needs it
+ *     has a *_workspace_bytes query.  Contents need not be initialised and are
+ *     undefined afterwards.  Calls sharing one workspace must be on one stream.
+ */
+#ifndef MP_H_
+#define MP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t mp_half;   /* IEEE binary16 bit pattern */
+typedef void*    mp_stream; /* hipStream_t */
+
+enum {
+    MP_OK            = 0,
+    MP_E_INVAL       = -1, /* null pointer, negative size, bad enum, misaligned pointer */
+    MP_E_UNSUPPORTED = -2, /* valid request this build has no kernel for */
+    MP_E_WORKSPACE   = -3, /* workspace missing or smaller than the *_workspace_bytes query */
+    MP_E_HIP         = -4  /* the HIP runtime refused a launch; see mp_last_error() */
+};
+
+const char* mp_last_error(void);
+int         mp_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Loss-scale state (Section 3.1, item 1).  Lives in device memory; every kernel that needs
+ * the scale, the overflow flag or the optimizer step count reads it there.
+ * ------------------------------------------------------------------------------------------ */
+#define MP_HISTORY 4096 /* ring length of the per-step log */
+
+enum { MP_SCALE_STATIC = 0, MP_SCALE_BACKOFF = 1 };
+
+typedef struct mp_scale_state {
+    float   scale;           /* S used by the current iteration                               */
+    float   inv_scale;       /* 1.0f / S                                                      */
+    float   min_scale;
+    float   max_scale;
+    int32_t mode;            /* MP_SCALE_STATIC | MP_SCALE_BACKOFF                            */
+    int32_t growth_interval; /* N: double S after N consecutive clean steps                   */
+    int32_t good_steps;      /* consecutive clean steps since the last change of S            */
+    int32_t found_inf;       /* nonzero: an inf/NaN was seen in this iteration's gradients    */
+    int32_t opt_step;        /* number of optimizer steps applied (Adam's t)                  */
+    int32_t total_steps;     /* iterations seen                                               */
+    int32_t skipped_steps;   /* iterations skipped because of overflow                        */
+    int32_t reserved;
+    float   hist_scale[MP_HISTORY];     /* S used at iteration i (mod MP_HISTORY)             */
+    int32_t hist_found_inf[MP_HISTORY]; /* overflow flag of iteration i (mod MP_HISTORY)      */
+} mp_scale_state;
+
+/* Fill *st (device) : S = init_scale, counters zero, log cleared.  min_scale <= init_scale <= max_scale,
+ * growth_interval >= 1 else MP_E_INVAL. */
+int mp_scale_state_init(mp_scale_state* st, int mode, float init_scale, int growth_interval,
+                        float min_scale, float max_scale, mp_stream stream);
+
+/* End of an iteration ("the optimizer inspects gradients at each iteration and scales the loss for
+ * the next iteration", Section 3.1).  Reads st->found_inf and then, on the device:
+ *   log (S, found_inf); total_steps++
+ *   overflow : skipped_steps++, good_steps = 0, BACKOFF: S = max(S/2, min_scale)
+ *   clean    : opt_step++, good_steps++, BACKOFF and good_steps == growth_interval:
+ *              S = min(2S, max_scale), good_steps = 0
+ *   inv_scale = 1/S; found_inf = 0.
+ * STATIC mode never changes S (an overflowing step is still skipped and counted). */
+int mp_loss_scale_update(mp_scale_state* st, mp_stream stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Dense contractions (Section 3.1: fp16 operands, fp32 accumulation, result stored in fp16).
+ * One descriptor serves the three calls of a linear layer  Y[M,N] = X[M,K] W[N,K]^T :
+ *     fwd    : Y  = epi(alpha * X W^T)          contraction over K
+ *     bwd_dx : dX = epi(alpha * dY W)           contraction over N
+ *     bwd_dw : dW = alpha * dY^T X              contraction over M (tokens)
+ * With trans_w != 0 the second operand is stored as W[K,N] instead (Y = X W): this is how the
+ * attention products Q K^T (trans_w = 0) and P V (trans_w = 1) and their gradients use the same
+ * entry points.  Batched use: batch_outer x batch_inner independent problems; operand t of batch
+ * (o, i) starts at t + o*s?_outer + i*s?_inner (elements).  Strides of 0 broadcast.
+ * Fast (MFMA) path needs 16-byte aligned base pointers and ld / batch strides that are multiples
+ * of 8 elements; anything else runs a slow scalar kernel with the same results contract.
+ * ------------------------------------------------------------------------------------------ */
+enum { MP_EPI_NONE = 0, MP_EPI_BIAS = 1, MP_EPI_BIAS_RELU = 2 };
+
+typedef struct mp_gemm_desc {
+    int32_t M, N, K;          /* Y is M x N, X is M x K, W is N x K (K x N when trans_w)          */
+    int32_t ldx, ldw, ldy;    /* leading dimensions of X (dX), W (dW), Y (dY), in elements        */
+    int32_t batch_outer, batch_inner; /* >= 1                                                    */
+    int64_t sx_outer, sx_inner;       /* batch strides of X / dX                                 */
+    int64_t sw_outer, sw_inner;       /* batch strides of W / dW                                 */
+    int64_t sy_outer, sy_inner;       /* batch strides of Y / dY                                 */
+    float   alpha;            /* scales the fp32 accumulator before the epilogue (e.g. 1/sqrt(dk)) */
+    int32_t epilogue;         /* fwd only: MP_EPI_*                                              */
+    int32_t trans_w;          /* 0: W[N,K];  1: W[K,N]                                           */
+    int32_t reserved;
+} mp_gemm_desc;
+
+/* Bytes of workspace mp_gemm_bwd_dw needs for this descriptor (split-K partials in fp32 and the
+ * column-sum partials of db).  mp_gemm_fwd / mp_gemm_bwd_dx need none. */
+size_t mp_gemm_bwd_dw_workspace_bytes(const mp_gemm_desc* desc /* host */, int with_db);
+
+/* Y = RNE16( act( alpha * X W^T + acc_in + bias ) ).
+ *   X, W, Y   device fp16.  bias[N] device fp16, required iff epilogue != MP_EPI_NONE.
+ *   acc_in    device fp32 [M, N] with leading dimension N, or NULL: added to the accumulator
+ *             (lets a contraction be split over two calls without an fp16 rounding between).
+ *   y_f32     device fp32 [M, N] ld N, or NULL: if given, the fp32 value alpha*X W^T + acc_in
+ *             is stored here instead, Y is not written, and the epilogue must be NONE.
+ * Batched problems do not support acc_in / y_f32. */
+int mp_gemm_fwd(const mp_gemm_desc* desc /* host */, const mp_half* X, const mp_half* W,
+                const mp_half* bias, const float* acc_in, mp_half* Y, float* y_f32,
+                mp_stream stream);
+
+/* dX = RNE16( RNE16( alpha * dY W  (.) [relu_src > 0] ) + add ).
+ *   relu_src  device fp16 [M, K] ld = ld_aux, or NULL: gradient of a ReLU whose stored output is
+ *             relu_src (entries where relu_src <= 0 are zeroed).
+ *   add       device fp16 [M, K] ld = ld_aux, or NULL: a second gradient flowing into the same
+ *             tensor (residual branch); the sum is rounded once more, as if the two tensors had
+ *             been stored and then added.
+ * relu_src and add share ld_aux and the batch strides of dX; they may not both be given. */
+int mp_gemm_bwd_dx(const mp_gemm_desc* desc /* host */, const mp_half* dY, const mp_half* W,
+                   const mp_half* relu_src, const mp_half* add, int32_t ld_aux, mp_half* dX,
+                   mp_stream stream);
+
+/* dW = RNE16( alpha * dY^T X ) (overwrites; there is no gradient accumulation across calls) and,
+ * if db != NULL, db[N] = RNE16( column sums of dY ) (unbatched only).
+ *   st        device, or NULL: if given, st->found_inf is set when any value written to dW or db
+ *             is inf/NaN (the gradient inspection of Section 3.1 done where the gradient is made).
+ *   ws        device workspace of at least mp_gemm_bwd_dw_workspace_bytes(desc, db != NULL). */
+int mp_gemm_bwd_dw(const mp_gemm_desc* desc /* host */, const mp_half* dY, const mp_half* X,
+                   mp_half* dW, mp_half* db, mp_scale_state* st, void* ws, size_t ws_bytes,
+                   mp_stream stream);
+
+/* db[cols] = RNE16( column sums (fp32) of dY[rows, cols] ); optional overflow flag as above.
+ * Workspace: mp_colsum_workspace_bytes(rows, cols). */
+size_t mp_colsum_workspace_bytes(int rows, int cols);
+int mp_colsum(int rows, int cols, const mp_half* dY, int ld, mp_half* db, mp_scale_state* st,
+              void* ws, size_t ws_bytes, mp_stream stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Losses: fp32 loss value (unscaled mean) and the loss-scaled fp16 seed gradient
+ * (Section 3.1 item 1).  S is read from st on the device.
+ * ------------------------------------------------------------------------------------------ */
+size_t mp_loss_workspace_bytes(int rows, int cols);
+
+/* loss = mean (y - target)^2 over rows x cols;  dy = RNE16( float(2 S / (rows cols)) * (y - target) ).
+ * y, target, dy: device fp16, common leading dimension ld.  loss: device fp32 scalar. */
+int mp_mse_scaled(int rows, int cols, const mp_half* y, const mp_half* target, int ld,
+                  const mp_scale_state* st, float* loss, mp_half* dy, void* ws, size_t ws_bytes,
+                  mp_stream stream);
+
+/* loss = mean over rows of (logsumexp(z) - z[target]), z = float(logits), max-subtracted, fp32;
+ * dlogits = RNE16( float(S / rows) * (softmax(z) - onehot(target)) ).
+ * A target outside [0, vocab) gives that row zero loss and zero gradient (the mean still divides
+ * by rows).  logits / dlogits share ld; dlogits may alias logits (in-place). */
+int mp_softmax_xent_scaled(int rows, int vocab, const mp_half* logits, int ld, const int32_t* targets,
+                           const mp_scale_state* st, float* loss, mp_half* dlogits, void* ws,
+                           size_t ws_bytes, mp_stream stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Bandwidth-bound layer pieces (fp32 arithmetic between fp16 storage points, Section 3.2).
+ * ------------------------------------------------------------------------------------------ */
+/* y = RNE16( LN(x + a) * gamma + beta ) over the last dimension d; a may be NULL.  The sum, mean,
+ * biased variance and 1/sqrt(var + eps) stay fp32; mean[rows], rstd[rows] (device fp32) are kept
+ * for the backward pass.  x, a, y contiguous [rows, d]. */
+int mp_layernorm_fwd(int rows, int d, const mp_half* x, const mp_half* a, const mp_half* gamma,
+                     const mp_half* beta, float eps, mp_half* y, float* mean, float* rstd,
+                     mp_stream stream);
+
+/* dz = RNE16( rstd (g - mean_d(g) - xhat mean_d(g xhat)) ), g = dy gamma, xhat = (x + a - mean) rstd;
+ * dgamma[d] = RNE16( sum_rows dy xhat ), dbeta[d] = RNE16( sum_rows dy ).  dz is the gradient of both
+ * x and a.  Optional overflow flag on dgamma/dbeta.  Workspace: mp_layernorm_bwd_workspace_bytes. */
+size_t mp_layernorm_bwd_workspace_bytes(int rows, int d);
+int mp_layernorm_bwd(int rows, int d, const mp_half* dy, const mp_half* x, const mp_half* a,
+                     const mp_half* gamma, const float* mean, const float* rstd, mp_half* dz,
+                     mp_half* dgamma, mp_half* dbeta, mp_scale_state* st, void* ws, size_t ws_bytes,
+                     mp_stream stream);
+
+/* Row softmax of attention scores: p = RNE16( softmax_fp32(s) ), rows x cols, contiguous rows of
+ * length cols with leading dimension ld (p may alias s). */
+int mp_softmax_fwd(int64_t rows, int cols, const mp_half* s, mp_half* p, int ld, mp_stream stream);
+/* ds = RNE16( p (dp - sum_j dp_j p_j) ); ds may alias dp. */
+int mp_softmax_bwd(int64_t rows, int cols, const mp_half* p, const mp_half* dp, mp_half* ds, int ld,
+                   mp_stream stream);
+
+/* LSTM cell, gate blocks ordered (i, f, g, o) in gates[B, 4H] (leading dimension ldg):
+ *   c = sigma(f) c_prev + sigma(i) tanh(g)   (fp32, never rounded),  h = RNE16( sigma(o) tanh(c) ).
+ * c_prev, c: device fp32 [B, H] contiguous.  h is written to h_out (ld ldh) and, if h_out2 != NULL,
+ * also to h_out2 (ld ldh2) - the next time step's [x, h] row block and the next layer's input. */
+int mp_lstm_cell_fwd(int B, int H, const mp_half* gates, int ldg, const float* c_prev, float* c,
+                     mp_half* h_out, int ldh, mp_half* h_out2, int ldh2, mp_stream stream);
+
+/* Backward of the cell for one time step.  dh = float(dh_a) + float(dh_b) (either may be NULL),
+ * dc (device fp32 [B,H]) carries the cell-state gradient in and out (in place):
+ *   do = dh tanh(c) so(1-so);  dc += dh so (1 - tanh(c)^2)
+ *   di = dc tanh(g) si(1-si);  df = dc c_prev sf(1-sf);  dg = dc si (1 - tanh(g)^2);  dc *= sf
+ *   dgates = RNE16([di, df, dg, do])   (leading dimension ldg, same as gates). */
+int mp_lstm_cell_bwd(int B, int H, const mp_half* gates, int ldg, const float* c_prev, const float* c,
+                     const mp_half* dh_a, int ld_a, const mp_half* dh_b, int ld_b, float* dc,
+                     mp_half* dgates, mp_stream stream);
+
+/* dst = RNE16(src), n elements (initial fp16 copies of masters and inputs). */
+int mp_cast_f32_to_f16(size_t n, const float* src, mp_half* dst, mp_stream stream);
+/* Fill n 32-bit words (a kernel, safe inside HIP graph capture). */
+int mp_fill_u32(size_t n, uint32_t value, void* dst, mp_stream stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Optimizer wrapper (Section 3.2) with the gradient inspection of Section 3.1 and the fp32-side
+ * regulariser of Section 3.3.
+ * ------------------------------------------------------------------------------------------ */
+enum { MP_OPT_SGD = 0, MP_OPT_ADAM = 1 };
+enum { MP_UPDATE_DEFAULT = 0,
+       MP_UPDATE_PRECHECKED = 1 /* every gradient was produced by a call given `st`: skip the
+                                   separate inspection pass and trust st->found_inf */ };
+
+typedef struct mp_tensor_desc {
+    const mp_half* g16; /* device: loss-scaled fp16 gradient                          */
+    float*         w32; /* device: fp32 master weights (updated in place)             */
+    mp_half*       w16; /* device: fp16 copy used by forward/backward (rewritten)     */
+    float*         m;   /* device: Adam first moment  (NULL for SGD)                  */
+    float*         v;   /* device: Adam second moment (NULL for SGD)                  */
+    size_t         n;   /* elements                                                   */
+} mp_tensor_desc;
+
+typedef struct mp_opt_cfg {
+    int32_t kind;         /* MP_OPT_SGD | MP_OPT_ADAM */
+    int32_t reserved;
+    double  lr;           /* hyper-parameters are given in double; the kernel uses their fp32   */
+    double  beta1, beta2; /* roundings, except that the bias corrections 1 - beta^t are formed  */
+    double  eps;          /* in double from the double betas and then rounded to fp32           */
+    double  weight_decay; /* L2 coefficient applied to the fp32 master: g += wd * w32           */
+} mp_opt_cfg;
+
+/* One call covers every parameter tensor, because the skip decision is global.
+ *   phase A: st->found_inf |= any fp16 gradient element with all exponent bits set (inf or NaN)
+ *            (skipped with MP_UPDATE_PRECHECKED);
+ *   phase B: if st->found_inf == 0, per element in fp32:
+ *            g = float(g16) * st->inv_scale + wd * w32
+ *            SGD : w32 -= lr g
+ *            Adam: m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;  t = st->opt_step + 1
+ *                  w32 -= lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
+ *            w16 = RNE16(w32)
+ *            else nothing is written.
+ * `tensors` is a host array of ntensors descriptors (device pointers inside), copied into kernel
+ * arguments during the call.  Does not advance opt_step or clear the flag: mp_loss_scale_update does. */
+int mp_unscale_check_update(const mp_tensor_desc* tensors /* host */, int ntensors,
+                            const mp_opt_cfg* cfg /* host */, mp_scale_state* st, int flags,
+                            mp_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MP_H_ */

@@ -1,0 +1,623 @@
+// fp16 x fp16 -> fp32-accumulate contractions on the gfx950 matrix cores (paper Section 3.1:
+// "math is done in FP16, results are accumulated in FP32"), with one RNE rounding to fp16 in the
+// epilogue.
+//
+// One kernel template serves forward, input-gradient and weight-gradient products.  Internally a
+// problem is  C[M,N] = alpha * sum_k A(m,k) B(n,k)  where each operand is either
+//   KC ("contraction-contiguous"):  A(m,k) = A[m*lda + k]
+//   OC ("output-contiguous")     :  A(m,k) = A[k*lda + m]
+// Tiles are staged through LDS in a k-contiguous, XOR-swizzled layout (rows of 64 halves =
+// 8 x 16-byte slots, slot index ^ f(row)), so that every matrix-core operand fragment is one
+// 16-byte LDS read per lane whatever the global layout; OC operands are transposed 8x8 in
+// registers (byte-permute instructions) between the global load and the LDS store.
+//
+// Matrix-core instruction: v_mfma_f32_32x32x16_f16.  The order of the 16 k-values inside one
+// instruction is irrelevant as long as both operands use the same one (a sum over k), so both
+// fragments are simply "8 consecutive k of one row".  Operands are issued swapped (B-tile rows as
+// the instruction's first operand), which makes each lane own 4 consecutive output columns of one
+// output row and allows 8-byte epilogue accesses:
+//     lane l, accumulator register r  ->  row m = l % 32,  col n = 8*(r/4) + 4*(l/32) + r%4.
+#include "common.hpp"
+
+#include <mutex>
+#include <cstring>
+
+namespace mp {
+
+constexpr int GEMM_THREADS = 256;
+constexpr int BK           = 64;  // halves per LDS row = 128 bytes = 8 slots of 16 bytes
+
+struct GemmArgs {
+    const uint16_t* A;
+    const uint16_t* B;
+    uint16_t*       C;
+    float*          C32;       // fp32 output (raw accumulator): y_f32 or split-K partials; ld = N
+    const float*    acc_in;    // fp32 addend, ld = N
+    const uint16_t* bias;      // [N]
+    const uint16_t* relu_src;  // [M,N] ld_aux: zero output where <= 0
+    const uint16_t* add;       // [M,N] ld_aux: second rounding after adding
+    int*            found_inf;
+    int             M, N, K;
+    int             lda, ldb, ldc, ld_aux;
+    long long       sa_o, sa_i, sb_o, sb_i, sc_o, sc_i;
+    int             batch_inner;
+    int             relu;
+    float           alpha;
+    int             k_per_split;  // multiple of BK; == K rounded up when not split
+    int             tiles_m, tiles_n;
+};
+
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+
+// 16-byte global load of 8 halves starting at p[0], of which only the first `valid` (0..8) exist.
+__device__ __forceinline__ uint4 load8_guard(const uint16_t* p, int valid) {
+    if (valid >= 8) return *reinterpret_cast<const uint4*>(p);
+    uint4 r = make_uint4(0, 0, 0, 0);
+    if (valid > 0) {
+        uint16_t* h = reinterpret_cast<uint16_t*>(&r);
+        for (int i = 0; i < valid; ++i) h[i] = p[i];
+    }
+    return r;
+}
+
+// ---- global -> registers.  R = tile rows (BM or BN).  Up to 8 x 16 bytes per lane.
+template <int R>
+struct KCLoader {  // operand stored [row][k]
+    static constexpr int NV = (R * 8 + GEMM_THREADS - 1) / GEMM_THREADS;  // vectors per lane
+    uint4                v[NV];
+    __device__ __forceinline__ void load(const uint16_t* base, int ld, int row0, int rows, int k0, int kend) {
+        const int kv = threadIdx.x & 7;
+        const int k  = k0 + kv * 8;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int r   = (threadIdx.x >> 3) + 32 * i;
+            const int row = row0 + r;
+            if (r < R && row < rows)
+                v[i] = load8_guard(base + (long long)row * ld + k, kend - k);
+            else
+                v[i] = make_uint4(0, 0, 0, 0);
+        }
+    }
+    __device__ __forceinline__ void store(char* lds) const {
+        const int kv = threadIdx.x & 7;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int r = (threadIdx.x >> 3) + 32 * i;
+            if (r < R) *reinterpret_cast<uint4*>(lds + r * 128 + ((kv ^ swz(r)) << 4)) = v[i];
+        }
+    }
+};
+
+template <int R>
+struct OCLoader {  // operand stored [k][row]: each active lane owns an 8(k) x 8(row) block
+    uint4                v[8];
+    __device__ __forceinline__ void load(const uint16_t* base, int ld, int row0, int rows, int k0, int kend) {
+        constexpr int G = R / 8;  // row groups
+        if ((int)threadIdx.x < R) {
+            const int rg = threadIdx.x % G, kg = threadIdx.x / G;
+            const int row = row0 + rg * 8;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int k = k0 + kg * 8 + j;
+                if (k < kend)
+                    v[j] = load8_guard(base + (long long)k * ld + row, rows - row);
+                else
+                    v[j] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    }
+    __device__ __forceinline__ void store(char* lds) const {
+        constexpr int G = R / 8;
+        if ((int)threadIdx.x < R) {
+            const int      rg = threadIdx.x % G, kg = threadIdx.x / G;
+            const unsigned in[8][4] = {{v[0].x, v[0].y, v[0].z, v[0].w}, {v[1].x, v[1].y, v[1].z, v[1].w},
+                                       {v[2].x, v[2].y, v[2].z, v[2].w}, {v[3].x, v[3].y, v[3].z, v[3].w},
+                                       {v[4].x, v[4].y, v[4].z, v[4].w}, {v[5].x, v[5].y, v[5].z, v[5].w},
+                                       {v[6].x, v[6].y, v[6].z, v[6].w}, {v[7].x, v[7].y, v[7].z, v[7].w}};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {  // output row i of the block = column i of the loaded block
+                unsigned o[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    // halves (k = 2p, row i) and (k = 2p+1, row i): low or high half of word i/2
+                    const unsigned lo = in[2 * p][i >> 1], hi = in[2 * p + 1][i >> 1];
+                    o[p] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                }
+                const int r = rg * 8 + i;
+                *reinterpret_cast<uint4*>(lds + r * 128 + ((kg ^ swz(r)) << 4)) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+        }
+    }
+};
+
+template <int R, bool KC>
+struct LoaderSel { typedef KCLoader<R> T; };
+template <int R>
+struct LoaderSel<R, false> { typedef OCLoader<R> T; };
+
+__device__ __forceinline__ f16x8 lds_frag(const char* lds, int row, int kv) {
+    return *reinterpret_cast<const f16x8*>(lds + row * 128 + ((kv ^ swz(row)) << 4));
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
+    static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
+    constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 matrix-core tiles per wave
+    static_assert(TM >= 1 && TN >= 1, "wave tile at least 32x32");
+    constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+
+    extern __shared__ __align__(16) char smem[];
+
+    // ---- which tile: spread consecutive workgroup ids (round-robin over the 8 XCDs) so that each
+    // XCD works on a contiguous run of tiles, then walk tiles in bands of GROUP tile-rows.
+    const int nb  = gridDim.x;
+    int       pid = blockIdx.x;
+    {
+        const int q = nb >> 3, rem = nb & 7, x = pid & 7, local = pid >> 3;
+        pid = x * q + min(x, rem) + local;
+    }
+    constexpr int GROUP = 4;
+    const int     band  = pid / (GROUP * g.tiles_n);
+    const int     first = band * GROUP;
+    const int     gsz   = min(GROUP, g.tiles_m - first);
+    const int     inb   = pid - band * GROUP * g.tiles_n;
+    const int     tile_m = first + inb % gsz;
+    const int     tile_n = inb / gsz;
+    const int     m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int bo = blockIdx.y / g.batch_inner, bi = blockIdx.y - bo * g.batch_inner;
+    const uint16_t* A = g.A + bo * g.sa_o + bi * g.sa_i;
+    const uint16_t* B = g.B + bo * g.sb_o + bi * g.sb_i;
+
+    const int kbeg = blockIdx.z * g.k_per_split;
+    const int kend = min(g.K, kbeg + g.k_per_split);
+    const int nkt  = (kend - kbeg + BK - 1) / BK;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    typename LoaderSel<BM, A_KC>::T la;
+    typename LoaderSel<BN, B_KC>::T lb;
+
+    if (nkt > 0) {
+        la.load(A, g.lda, m0, g.M, kbeg, kend);
+        lb.load(B, g.ldb, n0, g.N, kbeg, kend);
+        la.store(smem);
+        lb.store(smem + A_BYTES);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < nkt; ++kt) {
+        const char* sa = smem + (kt & 1) * STAGE;
+        const char* sb = sa + A_BYTES;
+        const bool  more = kt + 1 < nkt;
+        if (more) {
+            la.load(A, g.lda, m0, g.M, kbeg + (kt + 1) * BK, kend);
+            lb.load(B, g.ldb, n0, g.N, kbeg + (kt + 1) * BK, kend);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            f16x8     af[TM], bf[TN];
+            const int kv = kk * 2 + (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = lds_frag(sa, wm * WM + i * 32 + (lane & 31), kv);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bf[j] = lds_frag(sb, wn * WN + j * 32 + (lane & 31), kv);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[j], af[i], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            char* da = smem + ((kt + 1) & 1) * STAGE;
+            la.store(da);
+            lb.store(da + A_BYTES);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue
+    uint16_t*       C   = g.C ? g.C + bo * g.sc_o + bi * g.sc_i : nullptr;
+    const uint16_t* aux = g.relu_src ? g.relu_src : g.add;
+    if (aux) aux += bo * g.sc_o + bi * g.sc_i;
+    float* C32 = g.C32 ? g.C32 + (long long)blockIdx.z * g.M * g.N : nullptr;
+    bool   bad = false;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm * WM + i * 32 + (lane & 31);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * WN + j * 32 + q * 8 + (lane >> 5) * 4;
+                if (m >= g.M || n >= g.N) continue;
+                float     v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+                const int nv   = min(4, g.N - n);
+                if (C32) {  // raw accumulator out (split-K partial, or fp32 result with alpha and addend)
+                    float* dst = C32 + (long long)m * g.N + n;
+                    if (gridDim.z == 1) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] *= g.alpha;
+                        if (g.acc_in)
+                            for (int e = 0; e < nv; ++e) v[e] += g.acc_in[(long long)m * g.N + n + e];
+                    }
+                    if (nv == 4)
+                        *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                    else
+                        for (int e = 0; e < nv; ++e) dst[e] = v[e];
+                    continue;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] *= g.alpha;
+                if (g.acc_in) {
+                    if (nv == 4) {
+                        const float4 t = *reinterpret_cast<const float4*>(g.acc_in + (long long)m * g.N + n);
+                        v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+                    } else {
+                        for (int e = 0; e < nv; ++e) v[e] += g.acc_in[(long long)m * g.N + n + e];
+                    }
+                }
+                if (g.bias) {
+                    for (int e = 0; e < nv; ++e) v[e] += h2f(g.bias[n + e]);
+                }
+                if (g.relu) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+                }
+                uint16_t h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = f2h(v[e]);
+                if (aux) {
+                    const uint16_t* ap = aux + (long long)m * g.ld_aux + n;
+                    uint16_t        t[4] = {0, 0, 0, 0};
+                    if (nv == 4) {
+                        const uint2 raw = *reinterpret_cast<const uint2*>(ap);
+                        t[0] = raw.x & 0xFFFF; t[1] = raw.x >> 16; t[2] = raw.y & 0xFFFF; t[3] = raw.y >> 16;
+                    } else {
+                        for (int e = 0; e < nv; ++e) t[e] = ap[e];
+                    }
+                    if (g.relu_src) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (!(h2f(t[e]) > 0.f)) h[e] = 0;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) h[e] = f2h(h2f(h[e]) + h2f(t[e]));
+                    }
+                }
+                if (g.found_inf) {
+                    for (int e = 0; e < nv; ++e) bad |= half_nonfinite(h[e]);
+                }
+                uint16_t* dst = C + (long long)m * g.ldc + n;
+                if (nv == 4) {
+                    *reinterpret_cast<uint2*>(dst) =
+                        make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
+                } else {
+                    for (int e = 0; e < nv; ++e) dst[e] = h[e];
+                }
+            }
+        }
+    }
+    if (g.found_inf && __any(bad)) {
+        if (lane == 0) atomicOr(g.found_inf, 1);
+    }
+}
+
+// Sum split-K partials in split order, scale, round once, optional non-finite flag.
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ part, int splits, long long mn,
+                                                            int N, int ldc, float alpha, uint16_t* __restrict__ C,
+                                                            int* found_inf) {
+    bool bad = false;
+    for (long long v = (long long)blockIdx.x * 256 + threadIdx.x; v * 4 < mn; v += (long long)gridDim.x * 256) {
+        const long long e = v * 4;  // N % 4 == 0 on this path
+        float4          s = *reinterpret_cast<const float4*>(part + e);
+        for (int p = 1; p < splits; ++p) {
+            const float4 t = *reinterpret_cast<const float4*>(part + (long long)p * mn + e);
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+        const uint16_t  h0 = f2h(s.x * alpha), h1 = f2h(s.y * alpha), h2 = f2h(s.z * alpha), h3 = f2h(s.w * alpha);
+        const long long m = e / N, n = e - m * N;
+        *reinterpret_cast<uint2*>(C + m * ldc + n) =
+            make_uint2((unsigned)h0 | ((unsigned)h1 << 16), (unsigned)h2 | ((unsigned)h3 << 16));
+        bad |= half_nonfinite(h0) | half_nonfinite(h1) | half_nonfinite(h2) | half_nonfinite(h3);
+    }
+    if (found_inf && __any(bad)) {
+        if ((threadIdx.x & 63) == 0) atomicOr(found_inf, 1);
+    }
+}
+
+// Scalar kernel with the same contract, for shapes/alignments the matrix-core path does not take.
+__global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g, int a_kc, int b_kc) {
+    const long long mn  = (long long)g.M * g.N;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    bool            bad = false;
+    if (idx < mn) {
+        const int       m = (int)(idx / g.N), n = (int)(idx - (long long)m * g.N);
+        const int       bo = blockIdx.y / g.batch_inner, bi = blockIdx.y - bo * g.batch_inner;
+        const uint16_t* A = g.A + bo * g.sa_o + bi * g.sa_i;
+        const uint16_t* B = g.B + bo * g.sb_o + bi * g.sb_i;
+        float           acc = 0.f;
+        for (int k = 0; k < g.K; ++k) {
+            const float a = h2f(a_kc ? A[(long long)m * g.lda + k] : A[(long long)k * g.lda + m]);
+            const float b = h2f(b_kc ? B[(long long)n * g.ldb + k] : B[(long long)k * g.ldb + n]);
+            acc += a * b;
+        }
+        acc *= g.alpha;
+        if (g.acc_in) acc += g.acc_in[(long long)m * g.N + n];
+        if (g.C32) {
+            g.C32[(long long)m * g.N + n] = acc;
+        } else {
+            if (g.bias) acc += h2f(g.bias[n]);
+            if (g.relu) acc = fmaxf(acc, 0.f);
+            uint16_t        h = f2h(acc);
+            const long long coff = bo * g.sc_o + bi * g.sc_i;
+            if (g.relu_src) {
+                if (!(h2f(g.relu_src[coff + (long long)m * g.ld_aux + n]) > 0.f)) h = 0;
+            } else if (g.add) {
+                h = f2h(h2f(h) + h2f(g.add[coff + (long long)m * g.ld_aux + n]));
+            }
+            g.C[coff + (long long)m * g.ldc + n] = h;
+            bad = half_nonfinite(h);
+        }
+    }
+    if (g.found_inf && __any(bad)) {
+        if ((threadIdx.x & 63) == 0) atomicOr(g.found_inf, 1);
+    }
+}
+
+// ------------------------------------------------------------------------------------ host side
+struct TileCfg {
+    int   bm, bn;
+    float eff;  // relative per-flop efficiency of the tile shape (bigger tiles reuse LDS data more)
+};
+static const TileCfg kTiles[] = {{256, 256, 1.00f}, {256, 128, 0.85f}, {128, 256, 0.85f}, {128, 128, 0.65f},
+                                 {128, 64, 0.45f},  {64, 128, 0.45f},  {64, 64, 0.30f},   {32, 128, 0.25f}};
+constexpr int   kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+constexpr int   kCUs      = 256;
+
+template <int BM, int BN, int WM_, int WN_, bool AKC, bool BKC>
+static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t hs) {
+    constexpr size_t  lds = 2 * (size_t)(BM + BN) * 128;
+    static std::once_flag once;
+    static hipError_t     attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WM_, WN_, AKC, BKC>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    if (attr_err != hipSuccess) return hip_fail(attr_err, "gemm: hipFuncSetAttribute(LDS size)");
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM_, WN_, AKC, BKC>), grid, dim3(GEMM_THREADS), lds, hs, g);
+    MP_LAUNCH_CHECK("gemm launch");
+    return MP_OK;
+}
+
+template <bool AKC, bool BKC>
+static int launch_tile(int t, const GemmArgs& g, dim3 grid, hipStream_t hs) {
+    switch (t) {
+        case 0: return launch_one<256, 256, 2, 2, AKC, BKC>(g, grid, hs);
+        case 1: return launch_one<256, 128, 2, 2, AKC, BKC>(g, grid, hs);
+        case 2: return launch_one<128, 256, 2, 2, AKC, BKC>(g, grid, hs);
+        case 3: return launch_one<128, 128, 2, 2, AKC, BKC>(g, grid, hs);
+        case 4: return launch_one<128, 64, 2, 2, AKC, BKC>(g, grid, hs);
+        case 5: return launch_one<64, 128, 2, 2, AKC, BKC>(g, grid, hs);
+        case 6: return launch_one<64, 64, 2, 2, AKC, BKC>(g, grid, hs);
+        default: return launch_one<32, 128, 1, 4, AKC, BKC>(g, grid, hs);
+    }
+}
+
+struct Plan {
+    int tile, splits, k_per_split;
+};
+
+// Pick the tile shape (and split count when allowed) that minimises an estimate of run time:
+// rounds of 256 workgroups x work per workgroup / shape efficiency.
+static Plan make_plan(int M, int N, int K, long long batches, bool allow_split) {
+    Plan   best{0, 1, 0};
+    double best_cost = 1e300;
+    for (int t = 0; t < kNumTiles; ++t) {
+        const long long tm = (M + kTiles[t].bm - 1) / kTiles[t].bm, tn = (N + kTiles[t].bn - 1) / kTiles[t].bn;
+        const long long tiles = tm * tn * batches;
+        const int       max_s = allow_split ? 16 : 1;
+        for (int s = 1; s <= max_s; s *= 2) {
+            const int kps = ((K + s - 1) / s + BK - 1) / BK * BK;
+            if (s > 1 && (kps < 4 * BK || (long long)(s - 1) * kps >= K)) break;
+            const long long wgs    = tiles * s;
+            const long long rounds = (wgs + kCUs - 1) / kCUs;
+            double cost = (double)rounds * kTiles[t].bm * kTiles[t].bn * ((double)kps + 2.0 * BK) / kTiles[t].eff;
+            if (s > 1) cost += (double)M * N * s * 6.0;  // writing and re-reading fp32 partials
+            if (cost < best_cost) {
+                best_cost = cost;
+                best      = Plan{t, s, kps};
+            }
+        }
+    }
+    if (best.splits == 1) best.k_per_split = (K + BK - 1) / BK * BK;
+    if (best.k_per_split == 0) best.k_per_split = BK;
+    return best;
+}
+
+static bool fast_path_ok(const GemmArgs& g) {
+    auto m8 = [](long long v) { return (v & 7) == 0; };
+    if (!aligned16(g.A) || !aligned16(g.B)) return false;
+    if (g.C && !aligned16(g.C)) return false;
+    if (!m8(g.lda) || !m8(g.ldb) || !m8(g.ldc)) return false;
+    if (!m8(g.sa_o) || !m8(g.sa_i) || !m8(g.sb_o) || !m8(g.sb_i) || !m8(g.sc_o) || !m8(g.sc_i)) return false;
+    if ((g.relu_src || g.add) && (!m8(g.ld_aux) || !aligned16(g.relu_src) || !aligned16(g.add))) return false;
+    if (g.bias && !aligned16(g.bias)) return false;
+    if ((g.acc_in || g.C32) && ((g.N & 3) != 0 || !aligned16(g.acc_in) || !aligned16(g.C32))) return false;
+    return true;
+}
+
+// ws: split-K partial buffer (may be NULL when !allow_split).
+static int run_gemm(GemmArgs g, bool a_kc, bool b_kc, long long batches, bool allow_split, float* ws, size_t ws_floats,
+                    hipStream_t hs) {
+    if (g.M == 0 || g.N == 0 || batches == 0) return MP_OK;
+    if (!fast_path_ok(g) || batches > 65535) {
+        if (batches > 65535) {
+            set_error("gemm: more than 65535 batches");
+            return MP_E_UNSUPPORTED;
+        }
+        const long long mn = (long long)g.M * g.N;
+        g.k_per_split      = g.K;
+        hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)((mn + 255) / 256), (unsigned)batches), dim3(256), 0, hs, g,
+                           (int)a_kc, (int)b_kc);
+        MP_LAUNCH_CHECK("gemm (generic)");
+        return MP_OK;
+    }
+    Plan p = make_plan(g.M, g.N, g.K, batches, allow_split && ws != nullptr && (g.N & 3) == 0 && batches == 1);
+    if (p.splits > 1 && (size_t)p.splits * g.M * g.N > ws_floats) p = make_plan(g.M, g.N, g.K, batches, false);
+    g.k_per_split = p.k_per_split;
+    g.tiles_m     = (g.M + kTiles[p.tile].bm - 1) / kTiles[p.tile].bm;
+    g.tiles_n     = (g.N + kTiles[p.tile].bn - 1) / kTiles[p.tile].bn;
+    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n), (unsigned)batches, (unsigned)p.splits);
+
+    GemmArgs k = g;
+    if (p.splits > 1) {  // partials to workspace, epilogue in the finish kernel
+        k.C32       = ws;
+        k.C         = nullptr;
+        k.found_inf = nullptr;
+    }
+    int rc;
+    if (a_kc && b_kc) rc = launch_tile<true, true>(p.tile, k, grid, hs);
+    else if (a_kc && !b_kc) rc = launch_tile<true, false>(p.tile, k, grid, hs);
+    else if (!a_kc && !b_kc) rc = launch_tile<false, false>(p.tile, k, grid, hs);
+    else {
+        set_error("gemm: operand layout combination not built");
+        return MP_E_UNSUPPORTED;
+    }
+    if (rc != MP_OK) return rc;
+    if (p.splits > 1) {
+        const long long mn = (long long)g.M * g.N;
+        long long       nb = (mn / 4 + 255) / 256;
+        if (nb > 4096) nb = 4096;
+        hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)nb), dim3(256), 0, hs, ws, p.splits, mn, g.N, g.ldc, g.alpha,
+                           g.C, g.found_inf);
+        MP_LAUNCH_CHECK("gemm (split-K finish)");
+    }
+    return MP_OK;
+}
+
+static int check_desc(const mp_gemm_desc* d, const char* who) {
+    MP_REQUIRE(d != nullptr, "%s: desc is NULL", who);
+    MP_REQUIRE(d->M >= 0 && d->N >= 0 && d->K >= 0, "%s: negative dimension", who);
+    MP_REQUIRE(d->batch_outer >= 1 && d->batch_inner >= 1, "%s: batch counts must be >= 1", who);
+    MP_REQUIRE(d->trans_w == 0 || d->trans_w == 1, "%s: trans_w must be 0 or 1", who);
+    MP_REQUIRE(d->ldx >= d->K && d->ldy >= d->N && d->ldw >= (d->trans_w ? d->N : d->K),
+               "%s: leading dimension smaller than the row length (ldx=%d ldw=%d ldy=%d)", who, d->ldx, d->ldw, d->ldy);
+    MP_REQUIRE(d->sx_outer >= 0 && d->sx_inner >= 0 && d->sw_outer >= 0 && d->sw_inner >= 0 && d->sy_outer >= 0 &&
+                   d->sy_inner >= 0,
+               "%s: negative batch stride", who);
+    return MP_OK;
+}
+
+static void zero_args(GemmArgs& g) { g = GemmArgs{}; }
+
+}  // namespace mp
+
+using namespace mp;
+
+// fp32 partial-sum floats the weight-gradient product [M,N] with contraction K will use
+// (0 when the plan does not split the contraction).
+static size_t splitk_floats(int M, int N, int K) {
+    if (M <= 0 || N <= 0 || (N & 3) != 0) return 0;
+    const Plan p = make_plan(M, N, K, 1, true);
+    return p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N : 0;
+}
+
+extern "C" size_t mp_gemm_bwd_dw_workspace_bytes(const mp_gemm_desc* d, int with_db) {
+    if (!d) return 0;
+    const int rows = d->trans_w ? d->K : d->N, cols = d->trans_w ? d->N : d->K;
+    size_t    b    = 0;
+    if (d->batch_outer * (long long)d->batch_inner == 1) b = splitk_floats(rows, cols, d->M) * sizeof(float);
+    if (with_db) b += mp_colsum_workspace_bytes(d->M, d->N);
+    return b + 256;
+}
+
+extern "C" int mp_gemm_fwd(const mp_gemm_desc* d, const mp_half* X, const mp_half* W, const mp_half* bias,
+                           const float* acc_in, mp_half* Y, float* y_f32, mp_stream stream) {
+    int rc = check_desc(d, "mp_gemm_fwd");
+    if (rc) return rc;
+    MP_REQUIRE(X && W && (Y || y_f32), "mp_gemm_fwd: NULL operand");
+    MP_REQUIRE(d->epilogue >= MP_EPI_NONE && d->epilogue <= MP_EPI_BIAS_RELU, "mp_gemm_fwd: bad epilogue %d", d->epilogue);
+    MP_REQUIRE((d->epilogue == MP_EPI_NONE) == (bias == nullptr), "mp_gemm_fwd: bias must be given iff the epilogue uses it");
+    MP_REQUIRE(!(y_f32 && d->epilogue != MP_EPI_NONE), "mp_gemm_fwd: y_f32 needs MP_EPI_NONE");
+    const long long batches = (long long)d->batch_outer * d->batch_inner;
+    MP_REQUIRE(batches == 1 || (!acc_in && !y_f32), "mp_gemm_fwd: acc_in / y_f32 are not available for batched problems");
+    GemmArgs g;
+    zero_args(g);
+    g.A = X; g.B = W; g.C = y_f32 ? nullptr : Y; g.C32 = y_f32; g.acc_in = acc_in; g.bias = bias;
+    g.relu = d->epilogue == MP_EPI_BIAS_RELU;
+    g.M = d->M; g.N = d->N; g.K = d->K;
+    g.lda = d->ldx; g.ldb = d->ldw; g.ldc = d->ldy;
+    g.sa_o = d->sx_outer; g.sa_i = d->sx_inner; g.sb_o = d->sw_outer; g.sb_i = d->sw_inner;
+    g.sc_o = d->sy_outer; g.sc_i = d->sy_inner;
+    g.batch_inner = d->batch_inner; g.alpha = d->alpha;
+    return run_gemm(g, true, d->trans_w == 0, batches, false, nullptr, 0, as_stream(stream));
+}
+
+extern "C" int mp_gemm_bwd_dx(const mp_gemm_desc* d, const mp_half* dY, const mp_half* W, const mp_half* relu_src,
+                              const mp_half* add, int32_t ld_aux, mp_half* dX, mp_stream stream) {
+    int rc = check_desc(d, "mp_gemm_bwd_dx");
+    if (rc) return rc;
+    MP_REQUIRE(dY && W && dX, "mp_gemm_bwd_dx: NULL operand");
+    MP_REQUIRE(!(relu_src && add), "mp_gemm_bwd_dx: relu_src and add may not both be given");
+    MP_REQUIRE(!(relu_src || add) || ld_aux >= d->K, "mp_gemm_bwd_dx: ld_aux=%d smaller than K", ld_aux);
+    GemmArgs g;
+    zero_args(g);
+    g.A = dY; g.B = W; g.C = dX; g.relu_src = relu_src; g.add = add; g.ld_aux = ld_aux;
+    g.M = d->M; g.N = d->K; g.K = d->N;
+    g.lda = d->ldy; g.ldb = d->ldw; g.ldc = d->ldx;
+    g.sa_o = d->sy_outer; g.sa_i = d->sy_inner; g.sb_o = d->sw_outer; g.sb_i = d->sw_inner;
+    g.sc_o = d->sx_outer; g.sc_i = d->sx_inner;
+    g.batch_inner = d->batch_inner; g.alpha = d->alpha;
+    // W[N,K] read as B(n'=k, k'=n) is output-contiguous; W[K,N] is contraction-contiguous.
+    return run_gemm(g, true, d->trans_w == 1, (long long)d->batch_outer * d->batch_inner, false, nullptr, 0,
+                    as_stream(stream));
+}
+
+extern "C" int mp_gemm_bwd_dw(const mp_gemm_desc* d, const mp_half* dY, const mp_half* X, mp_half* dW, mp_half* db,
+                              mp_scale_state* st, void* ws, size_t ws_bytes, mp_stream stream) {
+    int rc = check_desc(d, "mp_gemm_bwd_dw");
+    if (rc) return rc;
+    MP_REQUIRE(dY && X && dW, "mp_gemm_bwd_dw: NULL operand");
+    const long long batches = (long long)d->batch_outer * d->batch_inner;
+    MP_REQUIRE(!(db && batches != 1), "mp_gemm_bwd_dw: db is not available for batched problems");
+    const size_t need = mp_gemm_bwd_dw_workspace_bytes(d, db != nullptr);
+    if (!ws || ws_bytes < need || !aligned16(ws)) {
+        set_error("mp_gemm_bwd_dw: 16-byte aligned workspace of %zu bytes needed, %zu given", need, ws_bytes);
+        return MP_E_WORKSPACE;
+    }
+    GemmArgs g;
+    zero_args(g);
+    g.C = dW; g.found_inf = st ? &st->found_inf : nullptr;
+    g.K = d->M;
+    g.ldc = d->ldw;
+    g.sc_o = d->sw_outer; g.sc_i = d->sw_inner;
+    g.batch_inner = d->batch_inner; g.alpha = d->alpha;
+    if (!d->trans_w) {  // dW[N,K] = dY^T X
+        g.A = dY; g.lda = d->ldy; g.sa_o = d->sy_outer; g.sa_i = d->sy_inner; g.M = d->N;
+        g.B = X;  g.ldb = d->ldx; g.sb_o = d->sx_outer; g.sb_i = d->sx_inner; g.N = d->K;
+    } else {  // dW[K,N] = X^T dY
+        g.A = X;  g.lda = d->ldx; g.sa_o = d->sx_outer; g.sa_i = d->sx_inner; g.M = d->K;
+        g.B = dY; g.ldb = d->ldy; g.sb_o = d->sy_outer; g.sb_i = d->sy_inner; g.N = d->N;
+    }
+    float*       wsf       = static_cast<float*>(ws);
+    const size_t sk_floats = batches == 1 ? splitk_floats(g.M, g.N, g.K) : 0;
+    rc = run_gemm(g, false, false, batches, sk_floats > 0, sk_floats > 0 ? wsf : nullptr, sk_floats, as_stream(stream));
+    if (rc) return rc;
+    if (db) {
+        char*  cs_ws = static_cast<char*>(ws) + ((sk_floats * sizeof(float) + 255) / 256) * 256;
+        size_t cs_b  = ws_bytes - (size_t)(cs_ws - static_cast<char*>(ws));
+        return mp_colsum(d->M, d->N, dY, d->ldy, db, st, cs_ws, cs_b, stream);
+    }
+    return MP_OK;
+}

@@ -1,0 +1,225 @@
+// Loss kernels: fp32 loss value and loss-scaled fp16 seed gradient (paper Section 3.1 item 1).
+// Both are streaming kernels bound by HBM: every fp16 input is read once and the fp16 seed
+// gradient written once; reductions are two-stage and deterministic (no float atomics).
+#include "common.hpp"
+
+namespace mp {
+
+constexpr int LOSS_THREADS = 256;
+
+// Sum `n` fp32 partials with one workgroup (fixed order), divide by `denom`, store to *out.
+__global__ __launch_bounds__(LOSS_THREADS) void finish_mean_kernel(const float* __restrict__ part, int n, double denom,
+                                                                   float* __restrict__ out) {
+    __shared__ float red[LOSS_THREADS / 64];
+    float            acc = 0.f;
+    for (int i = threadIdx.x; i < n; i += LOSS_THREADS) acc += part[i];
+    const float tot = block_sum<LOSS_THREADS / 64>(acc, red);
+    if (threadIdx.x == 0) *out = tot / (float)denom;
+}
+
+// ------------------------------------------------------------------------------- MSE
+template <bool VEC>
+__global__ __launch_bounds__(LOSS_THREADS) void mse_kernel(int rows, int cols, int ld, const uint16_t* __restrict__ y,
+                                                           const uint16_t* __restrict__ tg,
+                                                           const mp_scale_state* __restrict__ st,
+                                                           uint16_t* __restrict__ dy, float* __restrict__ part) {
+    __shared__ float red[LOSS_THREADS / 64];
+    const double     numel = (double)rows * (double)cols;
+    const float      coef  = (float)(2.0 * (double)st->scale / numel);
+    float            acc   = 0.f;
+    if (VEC) {
+        const int       vpr   = cols >> 3;  // vectors per row
+        const long long nvec  = (long long)rows * vpr;
+        for (long long v = (long long)blockIdx.x * LOSS_THREADS + threadIdx.x; v < nvec;
+             v += (long long)gridDim.x * LOSS_THREADS) {
+            const long long r   = v / vpr;
+            const long long off = r * ld + (v - r * vpr) * 8;
+            const uint4     a   = *reinterpret_cast<const uint4*>(y + off);
+            const uint4     b   = *reinterpret_cast<const uint4*>(tg + off);
+            const unsigned  aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+            unsigned        ow[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float d0 = h2f((uint16_t)(aw[k] & 0xFFFF)) - h2f((uint16_t)(bw[k] & 0xFFFF));
+                const float d1 = h2f((uint16_t)(aw[k] >> 16)) - h2f((uint16_t)(bw[k] >> 16));
+                acc += d0 * d0;
+                acc += d1 * d1;
+                ow[k] = (unsigned)f2h(coef * d0) | ((unsigned)f2h(coef * d1) << 16);
+            }
+            *reinterpret_cast<uint4*>(dy + off) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        }
+    } else {
+        const long long n = (long long)rows * cols;
+        for (long long e = (long long)blockIdx.x * LOSS_THREADS + threadIdx.x; e < n;
+             e += (long long)gridDim.x * LOSS_THREADS) {
+            const long long r   = e / cols;
+            const long long off = r * ld + (e - r * cols);
+            const float     d   = h2f(y[off]) - h2f(tg[off]);
+            acc += d * d;
+            dy[off] = f2h(coef * d);
+        }
+    }
+    const float tot = block_sum<LOSS_THREADS / 64>(acc, red);
+    if (threadIdx.x == 0) part[blockIdx.x] = tot;
+}
+
+// ------------------------------------------------------------------------------- softmax cross-entropy
+// One workgroup per row.  With CACHE the row's fp16 bits stay in registers (<= 16 x 16 B per lane,
+// i.e. vocab <= 32768) so HBM sees one read and one write of the row; otherwise the row is
+// re-read (it then comes from L2).
+constexpr int XENT_MAXV = 16;
+
+template <bool CACHE>
+__global__ __launch_bounds__(LOSS_THREADS) void xent_kernel(int vocab, int ld, const uint16_t* logits,
+                                                            const int32_t* __restrict__ targets,
+                                                            const mp_scale_state* __restrict__ st, int rows,
+                                                            uint16_t* dlogits,  // may alias logits
+                                                            float* __restrict__ row_loss) {
+    __shared__ float red[LOSS_THREADS / 64];
+    const int        row  = blockIdx.x;
+    const uint16_t*  z    = logits + (long long)row * ld;
+    uint16_t*        dz   = dlogits + (long long)row * ld;
+    const int        tgt  = targets[row];
+    const bool       valid = tgt >= 0 && tgt < vocab;
+    const float      coef = (float)((double)st->scale / (double)rows);
+    // read before the first barrier; every write to dlogits (which may alias logits) comes after it
+    const float      zt   = valid ? h2f(z[tgt]) : 0.f;
+
+    if (CACHE) {
+        const int nvec = vocab >> 3;
+        uint4     c[XENT_MAXV];
+        float     mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < XENT_MAXV; ++i) {
+            const int v = i * LOSS_THREADS + threadIdx.x;
+            if (v < nvec) {
+                c[i] = *reinterpret_cast<const uint4*>(z + (long long)v * 8);
+                const unsigned w[4] = {c[i].x, c[i].y, c[i].z, c[i].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    mx = fmaxf(mx, h2f((uint16_t)(w[k] & 0xFFFF)));
+                    mx = fmaxf(mx, h2f((uint16_t)(w[k] >> 16)));
+                }
+            }
+        }
+        mx = block_max<LOSS_THREADS / 64>(mx, red);
+        float se = 0.f;
+#pragma unroll
+        for (int i = 0; i < XENT_MAXV; ++i) {
+            const int v = i * LOSS_THREADS + threadIdx.x;
+            if (v < nvec) {
+                const unsigned w[4] = {c[i].x, c[i].y, c[i].z, c[i].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    se += __expf(h2f((uint16_t)(w[k] & 0xFFFF)) - mx);
+                    se += __expf(h2f((uint16_t)(w[k] >> 16)) - mx);
+                }
+            }
+        }
+        se = block_sum<LOSS_THREADS / 64>(se, red);
+        const float inv = 1.0f / se;
+        if (threadIdx.x == 0) row_loss[row] = valid ? (mx + __logf(se)) - zt : 0.f;
+#pragma unroll
+        for (int i = 0; i < XENT_MAXV; ++i) {
+            const int v = i * LOSS_THREADS + threadIdx.x;
+            if (v < nvec) {
+                const unsigned w[4] = {c[i].x, c[i].y, c[i].z, c[i].w};
+                unsigned       o[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int e0 = v * 8 + 2 * k;
+                    float     p0 = __expf(h2f((uint16_t)(w[k] & 0xFFFF)) - mx) * inv;
+                    float     p1 = __expf(h2f((uint16_t)(w[k] >> 16)) - mx) * inv;
+                    if (e0 == tgt) p0 -= 1.0f;
+                    if (e0 + 1 == tgt) p1 -= 1.0f;
+                    if (!valid) p0 = p1 = 0.f;
+                    o[k] = (unsigned)f2h(coef * p0) | ((unsigned)f2h(coef * p1) << 16);
+                }
+                *reinterpret_cast<uint4*>(dz + (long long)v * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+        }
+    } else {
+        float mx = -INFINITY;
+        for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) mx = fmaxf(mx, h2f(z[e]));
+        mx = block_max<LOSS_THREADS / 64>(mx, red);
+        float se = 0.f;
+        for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) se += __expf(h2f(z[e]) - mx);
+        se = block_sum<LOSS_THREADS / 64>(se, red);
+        const float inv = 1.0f / se;
+        if (threadIdx.x == 0) row_loss[row] = valid ? (mx + __logf(se)) - zt : 0.f;
+        for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) {
+            float p = __expf(h2f(z[e]) - mx) * inv;
+            if (e == tgt) p -= 1.0f;
+            if (!valid) p = 0.f;
+            dz[e] = f2h(coef * p);
+        }
+    }
+}
+
+}  // namespace mp
+
+using namespace mp;
+
+static int loss_blocks(long long units) {
+    long long b = (units + LOSS_THREADS * 4 - 1) / (LOSS_THREADS * 4);
+    if (b < 1) b = 1;
+    if (b > 2048) b = 2048;
+    return (int)b;
+}
+
+extern "C" size_t mp_loss_workspace_bytes(int rows, int cols) {
+    (void)cols;
+    const size_t a = 2048 * sizeof(float);
+    const size_t b = (size_t)(rows > 0 ? rows : 0) * sizeof(float);
+    return a > b ? a : b;
+}
+
+extern "C" int mp_mse_scaled(int rows, int cols, const mp_half* y, const mp_half* target, int ld,
+                             const mp_scale_state* st, float* loss, mp_half* dy, void* ws, size_t ws_bytes,
+                             mp_stream stream) {
+    MP_REQUIRE(rows > 0 && cols > 0 && ld >= cols, "mp_mse_scaled: bad shape rows=%d cols=%d ld=%d", rows, cols, ld);
+    MP_REQUIRE(y && target && st && loss && dy, "mp_mse_scaled: NULL argument");
+    if (!ws || ws_bytes < mp_loss_workspace_bytes(rows, cols)) {
+        set_error("mp_mse_scaled: workspace of %zu bytes needed, %zu given", mp_loss_workspace_bytes(rows, cols), ws_bytes);
+        return MP_E_WORKSPACE;
+    }
+    const bool vec = (cols % 8 == 0) && (ld % 8 == 0) && aligned16(y) && aligned16(target) && aligned16(dy);
+    const int  nb  = loss_blocks(vec ? (long long)rows * cols / 8 : (long long)rows * cols);
+    float*     part = static_cast<float*>(ws);
+    hipStream_t hs = as_stream(stream);
+    if (vec)
+        hipLaunchKernelGGL(mse_kernel<true>, dim3(nb), dim3(LOSS_THREADS), 0, hs, rows, cols, ld, y, target, st, dy, part);
+    else
+        hipLaunchKernelGGL(mse_kernel<false>, dim3(nb), dim3(LOSS_THREADS), 0, hs, rows, cols, ld, y, target, st, dy, part);
+    MP_LAUNCH_CHECK("mp_mse_scaled");
+    hipLaunchKernelGGL(finish_mean_kernel, dim3(1), dim3(LOSS_THREADS), 0, hs, part, nb, (double)rows * (double)cols, loss);
+    MP_LAUNCH_CHECK("mp_mse_scaled(finish)");
+    return MP_OK;
+}
+
+extern "C" int mp_softmax_xent_scaled(int rows, int vocab, const mp_half* logits, int ld, const int32_t* targets,
+                                      const mp_scale_state* st, float* loss, mp_half* dlogits, void* ws,
+                                      size_t ws_bytes, mp_stream stream) {
+    MP_REQUIRE(rows > 0 && vocab > 0 && ld >= vocab, "mp_softmax_xent_scaled: bad shape rows=%d vocab=%d ld=%d", rows,
+               vocab, ld);
+    MP_REQUIRE(logits && targets && st && loss && dlogits, "mp_softmax_xent_scaled: NULL argument");
+    if (!ws || ws_bytes < mp_loss_workspace_bytes(rows, vocab)) {
+        set_error("mp_softmax_xent_scaled: workspace of %zu bytes needed, %zu given", mp_loss_workspace_bytes(rows, vocab),
+                  ws_bytes);
+        return MP_E_WORKSPACE;
+    }
+    float*      row_loss = static_cast<float*>(ws);
+    hipStream_t hs       = as_stream(stream);
+    const bool  cache = (vocab % 8 == 0) && (ld % 8 == 0) && aligned16(logits) && aligned16(dlogits) &&
+                       (vocab / 8 <= XENT_MAXV * LOSS_THREADS);
+    if (cache)
+        hipLaunchKernelGGL(xent_kernel<true>, dim3(rows), dim3(LOSS_THREADS), 0, hs, vocab, ld, logits, targets, st, rows,
+                           dlogits, row_loss);
+    else
+        hipLaunchKernelGGL(xent_kernel<false>, dim3(rows), dim3(LOSS_THREADS), 0, hs, vocab, ld, logits, targets, st, rows,
+                           dlogits, row_loss);
+    MP_LAUNCH_CHECK("mp_softmax_xent_scaled");
+    hipLaunchKernelGGL(finish_mean_kernel, dim3(1), dim3(LOSS_THREADS), 0, hs, row_loss, rows, (double)rows, loss);
+    MP_LAUNCH_CHECK("mp_softmax_xent_scaled(finish)");
+    return MP_OK;
+}

@@ -1,0 +1,428 @@
+"""Per-kernel parity of the HIP library (through its C ABI) against the CPU oracle, element by element,
+on seeded inputs whose sizes span several tiles and ragged tails.  Tolerances (north-star): contraction and
+gradient outputs rel. Frobenius <= 1e-3, fp32 masters <= 1e-5, flags and scale sequence exact."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_1805_10387_amd as mp
+from paper_1805_10387_amd import _lib as ML
+import mp_inputs as I
+from oracle import MIXED
+from oracle import layers as L
+from oracle import optimizer as O
+from oracle.numerics import half_bits
+from gpu_util import *
+
+RNG = lambda s: np.random.default_rng(1000 + s)
+S16 = MIXED.store
+
+
+def make_state(mode=ML.MP_SCALE_BACKOFF, scale=2.0 ** 15, interval=10, smin=1.0, smax=2.0 ** 24):
+    st = mp.scale_state_alloc()
+    mp.mp_scale_state_init(st, mode, scale, interval, smin, smax)
+    return st
+
+
+# ------------------------------------------------------------------ contractions
+GEMM_SHAPES = [  # (M, N, K)
+    (64, 1024, 256), (64, 256, 1024),          # config-1 layers
+    (300, 200, 136), (257, 129, 72), (33, 520, 64), (512, 384, 1000), (8, 8, 8), (1, 40, 2048),
+    (640, 512, 512),
+]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("epi", ["none", "bias", "bias_relu"])
+def test_gemm_fwd(M, N, K, epi):
+    r = RNG(M + N + K)
+    x, w, b = S16(r.standard_normal((M, K))), S16(r.standard_normal((N, K)) * 0.1), S16(r.standard_normal(N))
+    ref = L.linear_fwd(MIXED, x, w, None if epi == "none" else b, relu=(epi == "bias_relu"))
+    y = empty16(M, N)
+    d = mp.gemm_desc(M, N, K, epilogue={"none": 0, "bias": 1, "bias_relu": 2}[epi])
+    mp.mp_gemm_fwd(d, h16(x), h16(w), None if epi == "none" else h16(b), None, y)
+    assert_close16(y, ref, 1e-3, max_ulp=1, what=f"fwd {M}x{N}x{K} {epi}")
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_bwd_dx_and_dw(M, N, K):
+    r = RNG(M * 3 + N + K)
+    x, w = S16(r.standard_normal((M, K))), S16(r.standard_normal((N, K)) * 0.1)
+    dy = S16(r.standard_normal((M, N)))
+    dx_ref, dw_ref, db_ref = L.linear_bwd(MIXED, dy, x, w)
+    d = mp.gemm_desc(M, N, K)
+    dx = empty16(M, K)
+    mp.mp_gemm_bwd_dx(d, h16(dy), h16(w), dx)
+    assert_close16(dx, dx_ref, 1e-3, max_ulp=1, what="dx")
+    dw, db = empty16(N, K), empty16(N)
+    st = make_state()
+    ws = ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, True))
+    mp.mp_gemm_bwd_dw(d, h16(dy), h16(x), dw, db, st, ws)
+    assert_close16(dw, dw_ref, 1e-3, max_ulp=1, what="dw")
+    assert_close16(db, db_ref, 1e-3, max_ulp=1, what="db")
+    assert mp.scale_state_read(st).found_inf == 0
+
+
+def test_gemm_dx_relu_mask_and_residual_add():
+    M, N, K = 200, 136, 264
+    r = RNG(7)
+    w, dy = S16(r.standard_normal((N, K)) * 0.1), S16(r.standard_normal((M, N)))
+    src = S16(np.maximum(r.standard_normal((M, K)), 0))
+    other = S16(r.standard_normal((M, K)))
+    base = MIXED.store(dy @ w)
+    d = mp.gemm_desc(M, N, K)
+    out = empty16(M, K)
+    mp.mp_gemm_bwd_dx(d, h16(dy), h16(w), out, relu_src=h16(src), ld_aux=K)
+    assert_close16(out, L.relu_mask(MIXED, base, src), 1e-3, max_ulp=1, what="dx relu")
+    assert np.all(np32(out)[src <= 0] == 0)
+    mp.mp_gemm_bwd_dx(d, h16(dy), h16(w), out, add=h16(other), ld_aux=K)
+    # one ulp of the intermediate rounding can exceed one ulp of the (possibly cancelling) sum: norm bound only
+    assert_close16(out, L.add_store(MIXED, base, other), 1e-3, what="dx add")
+
+
+def test_gemm_leading_dimensions_and_unaligned_fallback():
+    r = RNG(8)
+    M, N, K = 70, 90, 50                      # K, N not multiples of 8: slow path
+    x, w = S16(r.standard_normal((M, K))), S16(r.standard_normal((N, K)))
+    y = empty16(M, N)
+    mp.mp_gemm_fwd(mp.gemm_desc(M, N, K), h16(x), h16(w), None, None, y)
+    assert_close16(y, L.linear_fwd(MIXED, x, w), 1e-3, max_ulp=1, what="unaligned")
+    # ld > cols, aligned: views into wider buffers
+    M, N, K = 96, 72, 40
+    xb, wb = S16(r.standard_normal((M, 64))), S16(r.standard_normal((N, 48)))
+    yb = torch.full((M, 80), 7.0, dtype=torch.float16, device="cuda")
+    mp.mp_gemm_fwd(mp.gemm_desc(M, N, K, ldx=64, ldw=48, ldy=80), h16(xb), h16(wb), None, None, yb)
+    assert_close16(yb[:, :N], L.linear_fwd(MIXED, xb[:, :K], wb[:, :K]), 1e-3, max_ulp=1, what="ld")
+    assert torch.all(yb[:, N:] == 7.0)        # nothing written outside the N columns
+
+
+def test_gemm_fp32_addend_and_fp32_output():
+    r = RNG(9)
+    M, N, K1, K2 = 48, 264, 136, 72
+    x1, x2 = S16(r.standard_normal((M, K1))), S16(r.standard_normal((M, K2)))
+    w = S16(r.standard_normal((N, K1 + K2)) * 0.2)
+    b = S16(r.standard_normal(N))
+    ref = L.linear_fwd(MIXED, np.concatenate([x1, x2], 1), w, b)
+    part = empty32(M, N)
+    wd = h16(w)
+    mp.mp_gemm_fwd(mp.gemm_desc(M, N, K1, ldw=K1 + K2), h16(x1), wd, None, None, None, part)
+    y = empty16(M, N)
+    mp.mp_gemm_fwd(mp.gemm_desc(M, N, K2, ldw=K1 + K2, epilogue=1), h16(x2), wd[:, K1:], h16(b), part, y)
+    assert_close16(y, ref, 1e-3, max_ulp=1, what="split contraction")
+
+
+def test_gemm_attention_batched_strided():
+    """Q K^T, P V and their gradients on a fused qkv buffer, batch = (sequence, head), no copies."""
+    B, S, h, dk = 3, 40, 4, 64
+    d_model, T = h * dk, B * S
+    r = RNG(10)
+    qkv = S16(r.standard_normal((T, 3 * d_model)))
+    ctx_ref, cache = L.attention_fwd(MIXED, qkv, B, S, h)
+    q, k, v, p, alpha = cache
+    qkv_d = h16(qkv)
+    s_d = empty16(B, h, S, S)
+    ds = mp.gemm_desc(S, S, dk, ldx=3 * d_model, ldw=3 * d_model, ldy=S, alpha=float(alpha), batch_outer=B, batch_inner=h,
+                      sx=(S * 3 * d_model, dk), sw=(S * 3 * d_model, dk), sy=(h * S * S, S * S))
+    mp.mp_gemm_fwd(ds, qkv_d, qkv_d[:, d_model:], None, None, s_d)
+    s_ref = MIXED.store(alpha * (q @ k.transpose(0, 1, 3, 2)))
+    assert_close16(s_d, s_ref, 1e-3, max_ulp=1, what="scores")
+    p_d = empty16(B, h, S, S)
+    mp.mp_softmax_fwd(B * h * S, S, s_d, p_d, S)
+    assert_close16(p_d, p, 1e-3, max_ulp=2, what="softmax")
+    ctx_d = empty16(T, d_model)
+    dc = mp.gemm_desc(S, dk, S, ldx=S, ldw=3 * d_model, ldy=d_model, trans_w=1, batch_outer=B, batch_inner=h,
+                      sx=(h * S * S, S * S), sw=(S * 3 * d_model, dk), sy=(S * d_model, dk))
+    mp.mp_gemm_fwd(dc, p_d, qkv_d[:, 2 * d_model:], None, None, ctx_d)
+    assert_close16(ctx_d, ctx_ref, 1e-3, what="ctx")
+    # backward (from the oracle's p so that the comparison isolates these kernels)
+    dctx = S16(r.standard_normal((T, d_model)))
+    dqkv_ref = L.attention_bwd(MIXED, dctx, cache)
+    p_o, dctx_d = h16(p), h16(dctx)
+    dp_d, dqkv_d = empty16(B, h, S, S), empty16(T, 3 * d_model)
+    ws = ws_bytes(1 << 20)
+    mp.mp_gemm_bwd_dx(dc, dctx_d, qkv_d[:, 2 * d_model:], dp_d)                     # dP = dctx V^T
+    mp.mp_gemm_bwd_dw(dc, dctx_d, p_o, dqkv_d[:, 2 * d_model:], None, None, ws)      # dV = P^T dctx
+    ds_d = empty16(B, h, S, S)
+    mp.mp_softmax_bwd(B * h * S, S, p_o, dp_d, ds_d, S)
+    mp.mp_gemm_bwd_dx(ds, ds_d, qkv_d[:, d_model:], dqkv_d)                          # dQ = alpha dS K
+    mp.mp_gemm_bwd_dw(ds, ds_d, qkv_d, dqkv_d[:, d_model:], None, None, ws)          # dK = alpha dS^T Q
+    assert_close16(dqkv_d, dqkv_ref, 1e-3, what="dqkv")
+
+
+def test_gemm_overflow_gives_inf_and_dw_sets_flag():
+    M, N, K = 64, 64, 64
+    x = np.full((M, K), 200.0, np.float32)
+    w = np.full((N, K), 200.0, np.float32)
+    y = empty16(M, N)
+    mp.mp_gemm_fwd(mp.gemm_desc(M, N, K), h16(x), h16(w), None, None, y)
+    assert np.all(np.isposinf(np32(y)))                   # 64 * 4e4 overflows fp16: inf, never 65504
+    st = make_state()
+    d = mp.gemm_desc(M, N, K)
+    dw = empty16(N, K)
+    ws = ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, False))
+    mp.mp_gemm_bwd_dw(d, h16(x), h16(w), dw, None, st, ws)
+    assert mp.scale_state_read(st).found_inf == 1
+
+
+def test_gemm_split_k_weight_gradient():
+    M, N, K = 4096, 128, 256                  # small output, long token contraction: split over K
+    r = RNG(11)
+    x, dy = S16(r.standard_normal((M, K))), S16(r.standard_normal((M, N)) * 0.05)
+    d = mp.gemm_desc(M, N, K)
+    dw, db = empty16(N, K), empty16(N)
+    ws = ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, True))
+    mp.mp_gemm_bwd_dw(d, h16(dy), h16(x), dw, db, None, ws)
+    _, dw_ref, db_ref = L.linear_bwd(MIXED, dy, x, np.zeros((N, K), np.float32))
+    assert_close16(dw, dw_ref, 1e-3, max_ulp=1, what="split-K dw")
+    assert_close16(db, db_ref, 1e-3, max_ulp=1, what="db")
+
+
+def test_gemm_rejects_bad_arguments():
+    d = mp.gemm_desc(8, 8, 8)
+    with pytest.raises(mp.MPError) as e:
+        mp.mp_gemm_fwd(d, None, None, None, None, None)
+    assert e.value.code == ML.MP_E_INVAL
+    d2 = mp.gemm_desc(8, 8, 8, ldx=4)
+    with pytest.raises(mp.MPError):
+        mp.mp_gemm_fwd(d2, empty16(8, 8), empty16(8, 8), None, None, empty16(8, 8))
+    with pytest.raises(mp.MPError) as e:
+        mp.mp_gemm_bwd_dw(d, empty16(8, 8), empty16(8, 8), empty16(8, 8), None, None, None)
+    assert e.value.code == ML.MP_E_WORKSPACE
+
+
+# ------------------------------------------------------------------ losses
+@pytest.mark.parametrize("rows,cols", [(64, 256), (37, 100), (1, 8), (513, 1000)])
+def test_mse_scaled(rows, cols):
+    r = RNG(rows + cols)
+    y, t = S16(r.standard_normal((rows, cols))), S16(r.standard_normal((rows, cols)))
+    S = 2.0 ** 10
+    loss_ref, dy_ref = L.mse_scaled(MIXED, y, t, S)
+    st = make_state(scale=S)
+    loss, dy = empty32(1), empty16(rows, cols)
+    mp.mp_mse_scaled(rows, cols, h16(y), h16(t), cols, st, loss, dy, ws_bytes(mp.mp_loss_workspace_bytes(rows, cols)))
+    assert abs(float(loss) - float(loss_ref)) <= 1e-5 * abs(float(loss_ref))
+    assert_close16(dy, dy_ref, 1e-3, max_ulp=1, what="mse dy")
+
+
+@pytest.mark.parametrize("rows,vocab", [(16, 32768), (33, 3000), (7, 1001), (5, 40000)])
+def test_softmax_xent_scaled(rows, vocab):
+    r = RNG(rows + vocab)
+    z = S16(r.standard_normal((rows, vocab)) * 3)
+    t = r.integers(0, vocab, rows).astype(np.int32)
+    if rows > 4:
+        t[1], t[2] = -1, vocab                # out-of-range targets contribute nothing
+    S = 2.0 ** 15
+    loss_ref, g_ref = L.softmax_xent_scaled(MIXED, z, t, S)
+    st = make_state(scale=S)
+    loss, g = empty32(1), empty16(rows, vocab)
+    ws = ws_bytes(mp.mp_loss_workspace_bytes(rows, vocab))
+    zd = h16(z)
+    mp.mp_softmax_xent_scaled(rows, vocab, zd, vocab, i32(t), st, loss, g, ws)
+    assert abs(float(loss) - float(loss_ref)) <= 2e-6 * abs(float(loss_ref)) + 1e-6
+    assert_close16(g, g_ref, 1e-3, max_ulp=2, what="xent grad")
+    mp.mp_softmax_xent_scaled(rows, vocab, zd, vocab, i32(t), st, loss, zd, ws)   # in place
+    assert np.array_equal(bits(zd), bits(g))
+
+
+def test_xent_uniform_logits_closed_form():
+    rows, vocab = 8, 32768
+    st = make_state(scale=2.0 ** 15)
+    loss, g = empty32(1), empty16(rows, vocab)
+    z = torch.zeros(rows, vocab, dtype=torch.float16, device="cuda")
+    mp.mp_softmax_xent_scaled(rows, vocab, z, vocab, i32(np.arange(rows)), st, loss, g,
+                              ws_bytes(mp.mp_loss_workspace_bytes(rows, vocab)))
+    assert abs(float(loss) - 10.39720770839918) < 1e-5          # ln 32768
+
+
+# ------------------------------------------------------------------ LayerNorm / softmax / LSTM cell / colsum / cast
+@pytest.mark.parametrize("rows,d", [(64, 512), (203, 1024), (5, 8), (130, 2048), (31, 200)])
+def test_layernorm_fwd_bwd(rows, d):
+    r = RNG(rows + d)
+    x, a = S16(r.standard_normal((rows, d))), S16(r.standard_normal((rows, d)) * 0.5)
+    gam, bet = S16(1 + 0.2 * r.standard_normal(d)), S16(0.1 * r.standard_normal(d))
+    dy = S16(r.standard_normal((rows, d)))
+    y_ref, cache = L.layernorm_fwd(MIXED, x, a, gam, bet)
+    dz_ref, dg_ref, db_ref = L.layernorm_bwd(MIXED, dy, cache, gam)
+    xd, ad, gd, bd = h16(x), h16(a), h16(gam), h16(bet)
+    y, mean, rstd = empty16(rows, d), empty32(rows), empty32(rows)
+    mp.mp_layernorm_fwd(rows, d, xd, ad, gd, bd, L.LN_EPS, y, mean, rstd)
+    assert_close16(y, y_ref, 1e-3, max_ulp=1, what="ln y")
+    assert np.allclose(np32(rstd), cache[1][:, 0], rtol=1e-5)
+    dz, dg, db = empty16(rows, d), empty16(d), empty16(d)
+    st = make_state()
+    mp.mp_layernorm_bwd(rows, d, h16(dy), xd, ad, gd, mean, rstd, dz, dg, db, st,
+                        ws_bytes(mp.mp_layernorm_bwd_workspace_bytes(rows, d)))
+    assert_close16(dz, dz_ref, 1e-3, what="ln dz")
+    assert_close16(dg, dg_ref, 1e-3, max_ulp=1, what="ln dgamma")
+    assert_close16(db, db_ref, 1e-3, max_ulp=1, what="ln dbeta")
+    assert mp.scale_state_read(st).found_inf == 0
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 64), (1000, 128), (77, 40), (50, 256), (9, 512), (13, 301), (6, 1000)])
+def test_softmax_fwd_bwd(rows, cols):
+    r = RNG(rows + cols)
+    s = S16(r.standard_normal((rows, cols)) * 2)
+    p_ref = MIXED.store(L.softmax_rows(MIXED, s))
+    p = empty16(rows, cols)
+    mp.mp_softmax_fwd(rows, cols, h16(s), p, cols)
+    assert_close16(p, p_ref, 1e-3, max_ulp=2, what="softmax")
+    dp = S16(r.standard_normal((rows, cols)))
+    inner = (dp * p_ref).sum(-1, keepdims=True, dtype=np.float32)
+    ds_ref = MIXED.store(p_ref * (dp - inner))
+    ds = empty16(rows, cols)
+    mp.mp_softmax_bwd(rows, cols, h16(p_ref), h16(dp), ds, cols)
+    assert_close16(ds, ds_ref, 1e-3, what="softmax bwd")
+
+
+@pytest.mark.parametrize("B,H", [(32, 1024), (8, 128), (3, 50)])
+def test_lstm_cell_fwd_bwd(B, H):
+    r = RNG(B + H)
+    gates = S16(r.standard_normal((B, 4 * H)) * 2)
+    c_prev = (r.standard_normal((B, H))).astype(np.float32)
+    gi, gf, gg, go = (gates[:, j * H:(j + 1) * H] for j in range(4))
+    sg = lambda v: L._sigmoid(MIXED, v)
+    c_ref = sg(gf) * c_prev + sg(gi) * np.tanh(gg)
+    h_ref = MIXED.store(sg(go) * np.tanh(c_ref))
+    gd, cpd = h16(gates), f32(c_prev)
+    c, h1, h2 = empty32(B, H), empty16(B, H), torch.zeros(B, 2 * H + 8, dtype=torch.float16, device="cuda")
+    mp.mp_lstm_cell_fwd(B, H, gd, 4 * H, cpd, c, h1, H, h2[:, H:], 2 * H + 8)
+    assert np.allclose(np32(c), c_ref, rtol=2e-6, atol=2e-6)
+    assert_close16(h1, h_ref, 1e-3, max_ulp=1, what="h")
+    assert np.array_equal(bits(h2[:, H:2 * H].contiguous()), bits(h1)) and float(h2[:, :H].abs().sum()) == 0
+    # backward of the same step, checked against the oracle's formulas
+    dh_a, dh_b = S16(r.standard_normal((B, H))), S16(r.standard_normal((B, H)) * 0.3)
+    dc_in = r.standard_normal((B, H)).astype(np.float32)
+    one = np.float32(1)
+    si, sf, so, tg, tc = sg(gi), sg(gf), sg(go), np.tanh(gg), np.tanh(c_ref)
+    dh = dh_a + dh_b
+    d_o = dh * tc * so * (one - so)
+    dc = dc_in + dh * so * (one - tc * tc)
+    ref = MIXED.store(np.concatenate([dc * tg * si * (one - si), dc * c_prev * sf * (one - sf),
+                                      dc * si * (one - tg * tg), d_o], axis=1))
+    dcd, dg = f32(dc_in), empty16(B, 4 * H)
+    mp.mp_lstm_cell_bwd(B, H, gd, 4 * H, cpd, f32(c_ref), h16(dh_a), H, h16(dh_b), H, dcd, dg)
+    assert_close16(dg, ref, 1e-3, what="dgates")
+    assert np.allclose(np32(dcd), dc * sf, rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("rows,cols", [(4096, 512), (100, 40), (1, 8), (777, 1001), (8192, 64)])
+def test_colsum(rows, cols):
+    r = RNG(rows + cols)
+    dy = S16(r.standard_normal((rows, cols)))
+    db = empty16(cols)
+    mp.mp_colsum(rows, cols, h16(dy), cols, db, None, ws_bytes(mp.mp_colsum_workspace_bytes(rows, cols)))
+    assert_close16(db, MIXED.store(dy.sum(0, dtype=np.float32)), 1e-3, max_ulp=1, what="colsum")
+
+
+def test_cast_is_rne_and_overflows_to_inf():
+    r = RNG(12)
+    x = np.concatenate([r.standard_normal(100003).astype(np.float32) * np.float32(s) for s in (1e-7, 1e-3, 1, 7e4)])
+    x[:6] = [65520.0, 65519.99, 2.0 ** -25, np.nextafter(np.float32(2.0 ** -25), np.float32(1)), -1e9, np.nan]
+    out = empty16(x.size)
+    mp.mp_cast_f32_to_f16(x.size, f32(x), out)
+    ref = half_bits(MIXED.store(x))
+    got = bits(out)
+    nan = np.isnan(x)
+    assert np.array_equal(got[~nan], ref[~nan]) and np.all((got[nan] & 0x7C00) == 0x7C00)
+
+
+# ------------------------------------------------------------------ optimizer wrapper and scale policy
+def _tensors(r, sizes, adam=True):
+    out = []
+    for n in sizes:
+        out.append(dict(w=r.standard_normal(n).astype(np.float32) * 0.05, g=S16(r.standard_normal(n) * 100),
+                        m=r.standard_normal(n).astype(np.float32) * 0.01, v=np.abs(r.standard_normal(n)).astype(np.float32) * 1e-4))
+    return out
+
+
+def _run_update(ts, kind, S, t_prev, wd=0.0, poison=None, flags=0, lr=1e-3):
+    host = [dict(g16=t["g"].copy(), w32=t["w"].copy(), w16=MIXED.store(t["w"]), m=t["m"].copy(), v=t["v"].copy()) for t in ts]
+    if poison is not None:
+        host[poison[0]]["g16"][poison[1]] = poison[2]
+    ost = O.ScaleState(scale=S, opt_step=t_prev, growth_interval=3)
+    ocfg = I.OptCfg(kind=kind, lr=lr, weight_decay=wd)
+    dev = [dict(g16=h16(h["g16"]), w32=f32(h["w32"]), w16=h16(h["w16"]), m=f32(h["m"]), v=f32(h["v"])) for h in host]
+    found_ref = O.unscale_check_update(MIXED, host, ocfg, ost)
+    O.loss_scale_update(ost, found_ref)
+    st = make_state(scale=S, interval=3)
+    # bring the device state to the same optimizer step count
+    words = st.cpu()
+    words[8] = t_prev
+    st.copy_(words)
+    mp.mp_unscale_check_update(mp.tensor_list(dev), len(dev), mp.opt_cfg(kind, lr, weight_decay=wd), st, flags)
+    mp.mp_loss_scale_update(st)
+    return host, dev, ost, mp.scale_state_read(st), found_ref
+
+
+@pytest.mark.parametrize("kind", ["adam", "sgd"])
+@pytest.mark.parametrize("t_prev", [0, 1, 57])
+def test_update_matches_oracle(kind, t_prev):
+    sizes = [8192 * 3 + 5, 1, 7, 4096, 100000, 33] + [64] * 40          # > 32 tensors: several launches
+    ts = _tensors(RNG(20 + t_prev), sizes)
+    host, dev, ost, dst, found = _run_update(ts, kind, 2.0 ** 7, t_prev, wd=(1e-4 if kind == "sgd" else 0.0))
+    assert found == 0 and dst.opt_step == ost.opt_step == t_prev + 1
+    for h, d in zip(host, dev):
+        assert rel_fro(np32(d["w32"]), h["w32"]) <= 1e-5
+        assert np.abs(np32(d["w32"]) - h["w32"]).max() <= 1e-5 * np.abs(h["w32"]).max()
+        if kind == "adam":
+            assert rel_fro(np32(d["m"]), h["m"]) <= 1e-6 and rel_fro(np32(d["v"]), h["v"]) <= 1e-6
+        # the fp16 copy is exactly RNE16 of the master the device holds
+        assert np.array_equal(bits(d["w16"]), half_bits(MIXED.store(np32(d["w32"]))))
+
+
+@pytest.mark.parametrize("bad", [np.inf, -np.inf, np.nan])
+@pytest.mark.parametrize("where", [(0, 0), (2, 4095), (5, 32), (45, 63)])
+def test_update_skips_on_nonfinite_and_halves_scale(bad, where):
+    sizes = [8192 * 3 + 5, 1, 4096, 7, 100000, 33] + [64] * 40
+    ts = _tensors(RNG(30), sizes)
+    host, dev, ost, dst, found = _run_update(ts, "adam", 2.0 ** 15, 4, poison=(where[0], where[1], bad))
+    assert found == 1
+    assert (dst.scale, dst.good_steps, dst.opt_step, dst.skipped_steps, dst.found_inf) == (2.0 ** 14, 0, 4, 1, 0)
+    assert (ost.scale, ost.good_steps, ost.opt_step, ost.skipped_steps) == (2.0 ** 14, 0, 4, 1)
+    assert dst.hist_scale[0] == 2.0 ** 15 and dst.hist_found_inf[0] == 1
+    for t, d in zip(ts, dev):                 # every buffer byte-identical to before the call
+        assert np.array_equal(np32(d["w32"]).view(np.uint32), t["w"].view(np.uint32))
+        assert np.array_equal(np32(d["m"]).view(np.uint32), t["m"].view(np.uint32))
+        assert np.array_equal(np32(d["v"]).view(np.uint32), t["v"].view(np.uint32))
+        assert np.array_equal(bits(d["w16"]), half_bits(MIXED.store(t["w"])))
+
+
+def test_update_prechecked_flag_trusts_state():
+    ts = _tensors(RNG(31), [5000])
+    host, dev, ost, dst, found = _run_update(ts, "sgd", 4.0, 0, poison=(0, 17, np.inf), flags=ML.MP_UPDATE_PRECHECKED)
+    # the inspection pass was skipped and nobody had set the flag: the step is applied (inf reaches the master)
+    assert found == 1 and dst.opt_step == 1 and not np.isfinite(np32(dev[0]["w32"])[17])
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c4", "c5", "floor"])
+def test_scale_policy_sequences(name):
+    from test_oracle_optimizer import _golden
+    g = _golden()[name]
+    st = make_state(scale=g["s0"], interval=g["n"])
+    flag = torch.ones(1, dtype=torch.int32, device="cuda")
+    for step in range(g["steps"]):
+        if step in g["ovf"]:
+            st[7:8].copy_(flag)               # found_inf word, as a gradient-producing kernel would set it
+        mp.mp_loss_scale_update(st)
+    s = mp.scale_state_read(st)
+    assert list(s.hist_scale[:g["steps"]]) == g["seq"]
+    assert list(s.hist_found_inf[:g["steps"]]) == [int(i in g["ovf"]) for i in range(g["steps"])]
+    assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps, s.total_steps) == (g["final"], g["good"], g["t"], g["skipped"], g["steps"])
+    assert s.inv_scale == 1.0 / g["final"]
+
+
+def test_scale_state_static_mode_and_validation():
+    st = make_state(mode=ML.MP_SCALE_STATIC, scale=10.0, interval=1)
+    flag = torch.ones(1, dtype=torch.int32, device="cuda")
+    for f in (0, 1, 0, 0):
+        if f:
+            st[7:8].copy_(flag)
+        mp.mp_loss_scale_update(st)
+    s = mp.scale_state_read(st)
+    assert s.scale == 10.0 and s.skipped_steps == 1 and s.opt_step == 3 and s.inv_scale == np.float32(1.0) / np.float32(10.0)
+    with pytest.raises(mp.MPError):
+        mp.mp_scale_state_init(st, 1, 2.0, 0)
+    with pytest.raises(mp.MPError):
+        mp.mp_scale_state_init(st, 7, 2.0, 1)
