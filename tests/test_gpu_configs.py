@@ -1,0 +1,319 @@
+"""End-to-end parity of whole training iterations (HIP library through its C ABI) against the CPU oracle.
+
+Two protocols, both on the same seeded inputs:
+  * teacher-forced: at every step the oracle recomputes loss and gradients from the weights the GPU holds,
+    and re-applies the optimizer wrapper to the GPU's own pre-update state and gradients.  This checks each
+    iteration to the benchmark spec's tolerances (gradients rel. Frobenius <= 1e-3, masters <= 1e-5, flags/scale
+    state exact) without letting Adam's sign-like first steps amplify 1-ulp gradient differences.
+  * free-running: oracle and GPU train independently; the overflow flags, skipped steps and the loss-scale
+    sequence must agree exactly, losses closely.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_1805_10387_amd as mp
+from paper_1805_10387_amd import steps as St
+import mp_inputs as I
+from oracle import MIXED, FP64
+from oracle import layers as L
+from oracle import models as Mo
+from oracle import optimizer as O
+from oracle.numerics import half_bits
+from gpu_util import *
+
+GRAD_TOL, MASTER_TOL = 1e-3, 1e-5
+
+
+def _flat(wl):
+    m = wl.masters()
+    return Mo.flatten_layers(m) if isinstance(m, list) else m
+
+
+def _snapshot(step):
+    P = step.P
+    return dict(w16={k: np32(P.w16[k]) for k in P.names}, w32={k: np32(P.w32[k]) for k in P.names},
+                m={k: np32(P.m[k]) for k in P.names} if P.m else {}, v={k: np32(P.v[k]) for k in P.names} if P.v else {})
+
+
+def _f64(d):
+    return {k: (v if np.issubdtype(np.asarray(v).dtype, np.integer) else np.asarray(v, np.float64)) for k, v in d.items()}
+
+
+def teacher_forced(step, wl, fwd_bwd, batch, n_steps, inject_at=None, inject_name=None, expect_found=(),
+                   loss_tol=2e-4, batch_fn=None, grad_mode="direct"):
+    """grad_mode "direct": whole-network gradients within GRAD_TOL of the oracle's (holds where the network
+    has no discontinuity between the compared tensors and identical inputs).  "vs_fp64": for deep ReLU
+    stacks a 1-ulp difference in a stored activation flips ReLU masks and moves whole-network gradients by
+    ~1e-2 - exactly as far as the oracle itself sits from the fp64 definition - so the whole-network check
+    is that the GPU is as close to the fp64 gradients as the oracle is; the 1e-3 bound is then enforced op
+    by op on in-situ data (op_level_transformer)."""
+    names = step.P.names
+    worst = dict(grad=0.0, master=0.0)
+    for k in range(n_steps):
+        if batch_fn is not None:
+            batch = batch_fn(k)
+            step.set_batch(batch)
+        ob = Mo.island_batch(MIXED, batch)
+        before, s0 = _snapshot(step), step.state()
+        step.forward_backward()
+        if inject_at is not None and k == inject_at:
+            step.P.g16[inject_name].view(-1)[0:1].fill_(float("inf"))
+        g_gpu = {n: np32(step.P.g16[n]) for n in names}
+        loss_ref, g_ref = fwd_bwd(MIXED, before["w16"], ob, float(s0.scale))
+        if inject_at is not None and k == inject_at:
+            g_ref[inject_name].reshape(-1)[0] = np.inf
+        ref_bad = O.has_nonfinite(MIXED, list(g_ref.values()))
+        assert ref_bad == (k in expect_found), f"step {k}: oracle overflow={ref_bad}"
+        if np.isfinite(float(loss_ref)):
+            assert abs(float(step.loss) - float(loss_ref)) <= loss_tol * abs(float(loss_ref)), (k, float(step.loss), float(loss_ref))
+        else:
+            assert not np.isfinite(float(step.loss))
+        if not ref_bad and grad_mode == "direct":
+            for n in names:
+                e = rel_fro(g_gpu[n], g_ref[n])
+                worst["grad"] = max(worst["grad"], e)
+                assert e <= GRAD_TOL, f"step {k} grad {n}: rel Frobenius {e:.2e}"
+        elif not ref_bad:
+            _, g64 = fwd_bwd(FP64, _f64(before["w16"]), _f64(ob), float(s0.scale))
+            for n in names:
+                e_gpu, e_orc = rel_fro(g_gpu[n], g64[n]), rel_fro(g_ref[n], g64[n])
+                worst["grad"] = max(worst["grad"], e_gpu)
+                assert e_gpu <= 3.0 * e_orc + GRAD_TOL, f"step {k} grad {n}: GPU {e_gpu:.2e} vs oracle {e_orc:.2e} from fp64"
+        else:
+            assert O.has_nonfinite(MIXED, list(g_gpu.values()))
+        # oracle's optimizer wrapper on the GPU's own state and gradients
+        tensors = [dict(g16=g_gpu[n], w32=before["w32"][n].copy(), w16=before["w16"][n].copy(),
+                        m=before["m"].get(n, np.zeros(1, np.float32)).copy(), v=before["v"].get(n, np.zeros(1, np.float32)).copy())
+                   for n in names]
+        ost = O.ScaleState(mode=wl.scale.mode, scale=float(s0.scale), growth_interval=s0.growth_interval,
+                           min_scale=float(s0.min_scale), max_scale=float(s0.max_scale), good_steps=s0.good_steps,
+                           opt_step=s0.opt_step, total_steps=s0.total_steps, skipped_steps=s0.skipped_steps)
+        found = O.unscale_check_update(MIXED, tensors, wl.opt, ost)
+        O.loss_scale_update(ost, found)
+        step.optimizer()
+        s1, after = step.state(), _snapshot(step)
+        assert found == int(k in expect_found)
+        assert (s1.scale, s1.good_steps, s1.opt_step, s1.total_steps, s1.skipped_steps, s1.found_inf) == \
+               (ost.scale, ost.good_steps, ost.opt_step, ost.total_steps, ost.skipped_steps, 0), f"step {k} state"
+        assert s1.hist_scale[k] == s0.scale and s1.hist_found_inf[k] == found
+        for n, t in zip(names, tensors):
+            if found:
+                assert after["w32"][n].tobytes() == before["w32"][n].tobytes() and after["w16"][n].tobytes() == before["w16"][n].tobytes()
+                continue
+            e = rel_fro(after["w32"][n], t["w32"])
+            worst["master"] = max(worst["master"], e)
+            assert e <= MASTER_TOL, f"step {k} master {n}: {e:.2e}"
+            assert np.array_equal(half_bits(after["w16"][n]), half_bits(MIXED.store(after["w32"][n]))), f"w16 != RNE16(w32) for {n}"
+            if after["m"]:
+                assert rel_fro(after["m"][n], t["m"]) <= MASTER_TOL and rel_fro(after["v"][n], t["v"]) <= MASTER_TOL
+    return worst
+
+
+def free_running(step, wl, fwd_bwd, batch, n_steps, inject_at=None, inject_name=None, batch_fn=None, loss_tol=2e-3):
+    tr = Mo.Trainer(MIXED, _flat(wl), wl.opt, wl.scale)
+    losses = []
+    for k in range(n_steps):
+        if batch_fn is not None:
+            batch = batch_fn(k)
+            step.set_batch(batch)
+        inj_o = inj_g = None
+        if inject_at is not None and k == inject_at:
+            def inj_o(grads):
+                grads[inject_name].reshape(-1)[0] = np.inf
+
+            def inj_g(g16):
+                g16[inject_name].view(-1)[0:1].fill_(float("inf"))
+        tr.step(fwd_bwd, Mo.island_batch(MIXED, batch), inj_o)
+        step.step(inj_g)
+        losses.append(float(step.loss))
+    s = step.state()
+    assert [s.hist_scale[i] for i in range(n_steps)] == [h[0] for h in tr.state.history]
+    assert [s.hist_found_inf[i] for i in range(n_steps)] == [h[1] for h in tr.state.history]
+    assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (tr.state.scale, tr.state.good_steps, tr.state.opt_step, tr.state.skipped_steps)
+    assert np.allclose(losses, tr.losses, rtol=loss_tol, equal_nan=True), (losses, tr.losses)
+    return tr, losses
+
+
+# ------------------------------------------------------------------ config 1 (full size)
+def test_config1_teacher_forced():
+    wl = I.C1
+    step = St.MLPStep(wl)
+    batch = wl.batch()
+    step.set_batch(batch)
+    teacher_forced(step, wl, Mo.mlp_fwd_bwd, batch, wl.steps, inject_at=wl.inject_step, inject_name="w2",
+                   expect_found={wl.inject_step})
+
+
+def test_config1_free_running_sequence_and_masters():
+    from test_oracle_optimizer import _golden
+    wl = I.C1
+    step = St.MLPStep(wl)
+    batch = wl.batch()
+    step.set_batch(batch)
+    tr, losses = free_running(step, wl, Mo.mlp_fwd_bwd, batch, wl.steps, inject_at=wl.inject_step, inject_name="w2")
+    g = _golden()["c1"]
+    s = step.state()
+    assert [s.hist_scale[i] for i in range(20)] == g["seq"] and (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (g["final"], g["good"], g["t"], g["skipped"])
+    for n in ("w1", "w2"):                        # SGD: no sign-like amplification, masters stay within 1e-5
+        assert rel_fro(np32(step.P.w32[n]), tr.w32[n]) <= MASTER_TOL, n
+    for n in ("b1", "b2"):                        # zero-initialised: the master IS -lr * sum of gradients
+        assert rel_fro(np32(step.P.w32[n]), tr.w32[n]) <= GRAD_TOL, n
+
+
+# ------------------------------------------------------------------ configs 2, 3
+def op_level_transformer(step, wl, batch, tol=GRAD_TOL):
+    """One forward/backward on the GPU with every stored tensor captured; each operation of the oracle is then
+    evaluated on the GPU's own inputs of that operation and compared with the GPU's output of it."""
+    tr = {}
+    step.trace = lambda name, l, t: tr.__setitem__((name, l), np32(t))
+    w = {k: np32(step.P.w16[k]) for k in step.P.names}
+    scale = float(step.state().scale)
+    step.forward_backward()
+    step.trace = None
+    g = {k: np32(step.P.g16[k]) for k in step.P.names}
+    acts = [{k: np32(v) for k, v in a.items()} for a in step.act]
+    NB, S, h, d = wl.n_seq, wl.seq_len, wl.n_heads, wl.d_model
+    worst = [0.0]
+
+    def check(got, ref, what):
+        e = rel_fro(got, ref)
+        worst[0] = max(worst[0], e)
+        assert e <= tol, f"{what}: rel Frobenius {e:.2e}"
+
+    def heads(qkv):
+        return (L._heads(qkv[:, :d], NB, S, h), L._heads(qkv[:, d:2 * d], NB, S, h), L._heads(qkv[:, 2 * d:], NB, S, h))
+
+    x = np32(step.x0)
+    xs = []
+    alpha = np.float32(1.0 / np.sqrt(d // h))
+    for l in range(wl.n_layers):
+        a, p = acts[l], f"l{l}."
+        xs.append(x)
+        check(a["qkv"], L.linear_fwd(MIXED, x, w[p + "wqkv"], w[p + "bqkv"]), f"{l} qkv")
+        q, k, v = heads(a["qkv"])
+        check(tr[("s", l)], MIXED.store(alpha * (q @ k.transpose(0, 1, 3, 2))), f"{l} scores")
+        check(a["p"], MIXED.store(L.softmax_rows(MIXED, tr[("s", l)])), f"{l} softmax")
+        check(a["ctx"], L._unheads(MIXED.store(a["p"] @ v)), f"{l} ctx")
+        check(a["a"], L.linear_fwd(MIXED, a["ctx"], w[p + "wo"], w[p + "bo"]), f"{l} attn out")
+        y1, c1 = L.layernorm_fwd(MIXED, x, a["a"], w[p + "ln1_g"], w[p + "ln1_b"])
+        check(a["y1"], y1, f"{l} ln1")
+        check(a["rstd1"], c1[1][:, 0], f"{l} rstd1")
+        check(a["f"], L.linear_fwd(MIXED, a["y1"], w[p + "w1"], w[p + "b1"], relu=True), f"{l} ffn1")
+        check(a["g"], L.linear_fwd(MIXED, a["f"], w[p + "w2"], w[p + "b2"]), f"{l} ffn2")
+        y2, _ = L.layernorm_fwd(MIXED, a["y1"], a["g"], w[p + "ln2_g"], w[p + "ln2_b"])
+        check(a["y2"], y2, f"{l} ln2")
+        x = a["y2"]
+    loss_ref, dy_ref = L.mse_scaled(MIXED, x, np32(step.target), scale)
+    assert abs(float(step.loss) - float(loss_ref)) <= 1e-5 * float(loss_ref)
+    check(tr[("dy2", wl.n_layers - 1)], dy_ref, "seed gradient")
+    for l in range(wl.n_layers - 1, -1, -1):
+        a, p, x = acts[l], f"l{l}.", xs[l]
+        _, c2 = L.layernorm_fwd(MIXED, a["y1"], a["g"], w[p + "ln2_g"], w[p + "ln2_b"])
+        dz2, dg, db = L.layernorm_bwd(MIXED, tr[("dy2", l)], c2, w[p + "ln2_g"])
+        check(tr[("dz2", l)], dz2, f"{l} dz2"); check(g[p + "ln2_g"], dg, f"{l} dln2_g"); check(g[p + "ln2_b"], db, f"{l} dln2_b")
+        df, dw, db = L.linear_bwd(MIXED, tr[("dz2", l)], a["f"], w[p + "w2"])
+        check(g[p + "w2"], dw, f"{l} dw2"); check(g[p + "b2"], db, f"{l} db2")
+        check(tr[("df", l)], L.relu_mask(MIXED, df, a["f"]), f"{l} df")
+        dy1, dw, db = L.linear_bwd(MIXED, tr[("df", l)], a["y1"], w[p + "w1"])
+        check(g[p + "w1"], dw, f"{l} dw1"); check(g[p + "b1"], db, f"{l} db1")
+        check(tr[("dy1", l)], L.add_store(MIXED, dy1, tr[("dz2", l)]), f"{l} dy1")
+        _, c1 = L.layernorm_fwd(MIXED, x, a["a"], w[p + "ln1_g"], w[p + "ln1_b"])
+        dz1, dg, db = L.layernorm_bwd(MIXED, tr[("dy1", l)], c1, w[p + "ln1_g"])
+        check(tr[("dz1", l)], dz1, f"{l} dz1"); check(g[p + "ln1_g"], dg, f"{l} dln1_g"); check(g[p + "ln1_b"], db, f"{l} dln1_b")
+        dctx, dw, db = L.linear_bwd(MIXED, tr[("dz1", l)], a["ctx"], w[p + "wo"])
+        check(g[p + "wo"], dw, f"{l} dwo"); check(g[p + "bo"], db, f"{l} dbo"); check(tr[("dctx", l)], dctx, f"{l} dctx")
+        q, k, v = heads(a["qkv"])
+        dctx_h = L._heads(tr[("dctx", l)], NB, S, h)
+        check(tr[("dp", l)], MIXED.store(dctx_h @ v.transpose(0, 1, 3, 2)), f"{l} dp")
+        dpg, pg = tr[("dp", l)], a["p"]
+        check(tr[("ds", l)], MIXED.store(pg * (dpg - (dpg * pg).sum(-1, keepdims=True, dtype=np.float32))), f"{l} ds")
+        dsg = tr[("ds", l)]
+        dqkv = np.concatenate([L._unheads(MIXED.store(alpha * (dsg @ k))),
+                               L._unheads(MIXED.store(alpha * (dsg.transpose(0, 1, 3, 2) @ q))),
+                               L._unheads(MIXED.store(pg.transpose(0, 1, 3, 2) @ dctx_h))], axis=1)
+        check(tr[("dqkv", l)], dqkv, f"{l} dqkv")
+        dxa, dw, db = L.linear_bwd(MIXED, tr[("dqkv", l)], x, w[p + "wqkv"])
+        check(g[p + "wqkv"], dw, f"{l} dwqkv"); check(g[p + "bqkv"], db, f"{l} dbqkv")
+        check(tr[("dx", l)], L.add_store(MIXED, dxa, tr[("dz1", l)]), f"{l} dx")
+    return worst[0]
+
+
+def _transformer(wl, n_tf, n_free, **kw):
+    f = Mo.make_transformer_fwd_bwd(wl.n_layers, wl.n_seq, wl.seq_len, wl.n_heads)
+    batch = wl.batch()
+    step = St.TransformerStep(wl, **kw)
+    step.set_batch(batch)
+    op_level_transformer(step, wl, batch)
+    worst = teacher_forced(step, wl, f, batch, n_tf, grad_mode="vs_fp64")
+    if n_free:
+        step2 = St.TransformerStep(wl, **kw)
+        step2.set_batch(batch)
+        free_running(step2, wl, f, batch, n_free)
+    return worst
+
+
+def test_config2_reduced_size():
+    _transformer(I.C2_SMALL, 6, I.C2_SMALL.steps)
+
+
+def test_config3_reduced_size_two_layers():
+    _transformer(I.C3_SMALL, 3, 3)
+
+
+def test_config3_reduced_prechecked_flat_update_matches_default():
+    """The bench launch configuration (producer-side inspection, one flat descriptor) gives the same bits."""
+    wl, batch = I.C3_SMALL, I.C3_SMALL.batch()
+    a, b = St.TransformerStep(wl), St.TransformerStep(wl, prechecked=True, flat_update=True)
+    for s in (a, b):
+        s.set_batch(batch)
+        for _ in range(3):
+            s.step()
+    assert torch.equal(a.P.w32_arena, b.P.w32_arena) and torch.equal(a.P.w16_arena, b.P.w16_arena)
+    assert float(a.loss) == float(b.loss)
+
+
+def test_config2_full_size():
+    wl = replace(I.C2, steps=12)
+    _transformer(wl, 2, 12)                      # growth at step 10 is inside the free run
+
+
+# ------------------------------------------------------------------ config 4
+def _xent_batches(wl):
+    base = wl.batch()
+
+    def batch_fn(k):
+        b = dict(base)
+        if k == wl.blowup_step:
+            h = base["h"].copy()
+            h[0] *= wl.blowup_factor
+            b["h"] = h
+        return b
+    return batch_fn
+
+
+def test_config4_reduced_size():
+    wl = I.C4_SMALL
+    step = St.XentStep(wl)
+    teacher_forced(step, wl, Mo.xent_head_fwd_bwd, None, wl.steps, expect_found={wl.blowup_step}, batch_fn=_xent_batches(wl))
+    step2 = St.XentStep(wl)
+    free_running(step2, wl, Mo.xent_head_fwd_bwd, None, wl.steps, batch_fn=_xent_batches(wl))
+    s = step2.state()
+    assert [s.hist_found_inf[i] for i in range(wl.steps)] == [int(i == wl.blowup_step) for i in range(wl.steps)]
+
+
+# ------------------------------------------------------------------ config 5
+def test_config5_reduced_size():
+    wl = I.C5_SMALL
+    f = Mo.make_lstm_fwd_bwd(wl.n_layers)
+    batch = wl.batch()
+    step = St.LSTMStep(wl)
+    step.set_batch(batch)
+    teacher_forced(step, wl, f, batch, 4)
+    step2 = St.LSTMStep(wl)
+    step2.set_batch(batch)
+    free_running(step2, wl, f, batch, wl.steps)
