@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Throughput of the mixed-precision training step (config 3: Transformer-big layer stack) on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One "step" is the whole hot path over one synthetic batch already resident in HBM: 6 encoder layers
+forward, MSE loss with the loss-scaled seed gradient, backward (all dX and dW contractions), the fused
+unscale / overflow-check / Adam update of the fp32 masters with the fp16 re-cast, and the loss-scale
+update.  The step is captured once in a HIP graph and replayed K times between two events.
+
+Prints ONE JSON line with tokens/s plus
+  roofline        : the dense fp16 MFMA contractions of the step (per-launch flops / per-launch time
+                    measured with HIP events on the launch stream) against the fp16 dense peak
+  roofline_update : the fused optimizer kernel against peak HBM bandwidth
+  cpu_baseline    : the NumPy oracle timed on this host on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from dataclasses import replace
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP16_TFLOPS = 2500.0   # MI355X dense fp16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def _time_calls(torch, fn, reps):
+    """Average duration (s) of fn() launched reps times back to back on the current stream."""
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def gemm_roofline(torch, B, step, reps=20):
+    """Time each distinct dense contraction of one layer in isolation (same descriptors, same buffers as
+    the step uses) and aggregate: algorithmic flops = 2 M N K per launch."""
+    wl, w, g, a = step.wl, step.P.w16, step.P.g16, step.act[0]
+    T, d, f = wl.tokens, wl.d_model, wl.d_ff
+    x, ws, st = step.x0, step.ws, step.st
+    calls = {
+        "fwd_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_fwd(step.d_qkv, x, w["l0.wqkv"], w["l0.bqkv"], None, a["qkv"])),
+        "fwd_o": (2.0 * T * d * d, lambda: B.mp_gemm_fwd(step.d_o, a["ctx"], w["l0.wo"], w["l0.bo"], None, a["a"])),
+        "fwd_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_fwd(step.d_f1, a["y1"], w["l0.w1"], w["l0.b1"], None, a["f"])),
+        "fwd_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_fwd(step.d_f2, a["f"], w["l0.w2"], w["l0.b2"], None, a["g"])),
+        "dx_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dx(step.d_qkv, step.dqkv, w["l0.wqkv"], step.gbuf[1], add=step.dz1, ld_aux=d)),
+        "dx_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dx(step.d_o, step.dz1, w["l0.wo"], step.dctx)),
+        "dx_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f1, step.df, w["l0.w1"], step.dy1, add=step.dz2, ld_aux=d)),
+        "dx_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f2, step.dz2, w["l0.w2"], step.df, relu_src=a["f"], ld_aux=f)),
+        "dw_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dw(step.d_qkv, step.dqkv, x, g["l0.wqkv"], None, st, ws)),
+        "dw_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dw(step.d_o, step.dz1, a["ctx"], g["l0.wo"], None, st, ws)),
+        "dw_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f1, step.df, a["y1"], g["l0.w1"], None, st, ws)),
+        "dw_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f2, step.dz2, a["f"], g["l0.w2"], None, st, ws)),
+    }
+    per, flops, secs = {}, 0.0, 0.0
+    for name, (fl, fn) in calls.items():
+        t = _time_calls(torch, fn, reps)
+        per[name] = {"us": round(t * 1e6, 2), "tflops": round(fl / t * 1e-12, 1)}
+        flops += fl
+        secs += t
+    return flops, secs, per
+
+
+def cpu_baseline(wl, seconds_hint=20.0):
+    """The oracle, as it stands, on a bounded sample of config 3: all 6 layers at full width, 16 of the 64
+    sequences (2048 of 8192 tokens), complete iterations (forward, loss, backward, Adam on masters)."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import MIXED
+    from oracle import models as Mo
+    sample = replace(wl, n_seq=16)
+    masters = Mo.flatten_layers(sample.masters())
+    tr = Mo.Trainer(MIXED, masters, sample.opt, sample.scale)
+    f = Mo.make_transformer_fwd_bwd(sample.n_layers, sample.n_seq, sample.seq_len, sample.n_heads)
+    batch = Mo.island_batch(MIXED, sample.batch())
+    times = []
+    t_start = time.perf_counter()
+    while len(times) < 2 or (time.perf_counter() - t_start < seconds_hint and len(times) < 6):
+        t0 = time.perf_counter()
+        tr.step(f, batch)
+        times.append(time.perf_counter() - t0)
+    best = min(times)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": sample.tokens / best, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{sample.n_layers} layers x {sample.n_seq} of {wl.n_seq} sequences ({sample.tokens} tokens), "
+                      f"{len(times)} full iterations, best {best:.2f} s/iteration"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
+              "How the step would shard over several GPUs is described in DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import mp_inputs as I
+    import paper_1805_10387_amd as mp
+    from paper_1805_10387_amd import binding as B
+    from paper_1805_10387_amd import steps as St
+
+    torch.cuda.set_device(0)
+    wl = I.C3
+    step = St.TransformerStep(wl, prechecked=True, flat_update=True)
+    step.set_batch(wl.batch())
+    for _ in range(max(args.warmup, 1)):
+        step.step()
+    torch.cuda.synchronize()
+
+    if args.no_graph:
+        run = step.step
+    else:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step.step()
+        run = graph.replay
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    tokens_per_s = wl.tokens / (ms_per_step * 1e-3)
+    st = step.state()
+    loss = float(step.loss)
+
+    # ---- roofline of the dominant kernels, timed live with events on the launch stream
+    flops, secs, per = gemm_roofline(torch, B, step)
+    n_params = step.P.total                       # elements the flat update descriptor covers
+    upd_bytes = 28.0 * n_params
+    t_upd = _time_calls(torch, lambda: B.mp_unscale_check_update(step.P.flat_list, 1, step.cfg, step.st, 1), 10)
+    t_upd_chk = _time_calls(torch, lambda: B.mp_unscale_check_update(step.P.flat_list, 1, step.cfg, step.st, 0), 10)
+
+    out = {
+        "metric": "training tokens/sec (fp16 MP step, Transformer-big layer); MFMA util %",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "config 3: Transformer-big stack, 6 layers, d_model 1024, 16 heads, d_ff 4096, "
+                               "64 sequences x 128 tokens = 8192 tokens, fp16 with fp32 masters, MSE, Adam, "
+                               "dynamic loss scale 2^15 / growth 100",
+                   "launch": "HIP graph replay" if not args.no_graph else "eager ctypes launches",
+                   "overflow_check": "in gradient-producing epilogues (MP_UPDATE_PRECHECKED)", "update_list": "one flat descriptor"},
+        "step_gemm_tflops": wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12,
+        "step_mfma_util_pct": 100.0 * wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12 / PEAK_FP16_TFLOPS,
+        "final_loss": loss, "loss_scale": st.scale, "opt_steps": st.opt_step, "skipped": st.skipped_steps,
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (dense fp16 contractions of one layer: 4 fwd, 4 dX, 4 dW)",
+                     "achieved": flops / secs * 1e-12, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / secs * 1e-12 / PEAK_FP16_TFLOPS, "traffic": None,
+                     "flops_per_launch_set": flops, "per_call": per},
+        "roofline_update": {"bound": "hbm", "kernel": "update_kernel<ADAM> (unscale + Adam + fp16 re-cast)",
+                            "achieved": upd_bytes / t_upd * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": upd_bytes / t_upd * 1e-9 / PEAK_HBM_GBS, "traffic": None,
+                            "bytes_per_launch": upd_bytes, "us": t_upd * 1e6,
+                            "with_inspection_pass_us": t_upd_chk * 1e6,
+                            "with_inspection_pass_GBs": (upd_bytes + 2.0 * n_params) / t_upd_chk * 1e-9},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -52,12 +52,17 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 // 16-byte global load of 8 halves starting at p[0], of which only the first `valid` (0..8) exist.
 __device__ __forceinline__ uint4 load8_guard(const uint16_t* p, int valid) {
     if (valid >= 8) return *reinterpret_cast<const uint4*>(p);
-    uint4 r = make_uint4(0, 0, 0, 0);
-    if (valid > 0) {
-        uint16_t* h = reinterpret_cast<uint16_t*>(&r);
-        for (int i = 0; i < valid; ++i) h[i] = p[i];
-    }
-    return r;
+    // ragged tail: element loads, assembled with compile-time indices only (no addressable local)
+    unsigned w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+    if (valid > 0) w0 |= (unsigned)p[0];
+    if (valid > 1) w0 |= (unsigned)p[1] << 16;
+    if (valid > 2) w1 |= (unsigned)p[2];
+    if (valid > 3) w1 |= (unsigned)p[3] << 16;
+    if (valid > 4) w2 |= (unsigned)p[4];
+    if (valid > 5) w2 |= (unsigned)p[5] << 16;
+    if (valid > 6) w3 |= (unsigned)p[6];
+    if (valid > 7) w3 |= (unsigned)p[7] << 16;
+    return make_uint4(w0, w1, w2, w3);
 }
 
 // ---- global -> registers.  R = tile rows (BM or BN).  Up to 8 x 16 bytes per lane.
@@ -181,9 +186,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     typename LoaderSel<BM, A_KC>::T la;
     typename LoaderSel<BN, B_KC>::T lb;
@@ -248,13 +251,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
                     if (gridDim.z == 1) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] *= g.alpha;
-                        if (g.acc_in)
-                            for (int e = 0; e < nv; ++e) v[e] += g.acc_in[(long long)m * g.N + n + e];
+                        if (g.acc_in) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (e < nv) v[e] += g.acc_in[(long long)m * g.N + n + e];
+                        }
                     }
-                    if (nv == 4)
+                    if (nv == 4) {
                         *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-                    else
-                        for (int e = 0; e < nv; ++e) dst[e] = v[e];
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (e < nv) dst[e] = v[e];
+                    }
                     continue;
                 }
 #pragma unroll
@@ -264,11 +273,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
                         const float4 t = *reinterpret_cast<const float4*>(g.acc_in + (long long)m * g.N + n);
                         v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
                     } else {
-                        for (int e = 0; e < nv; ++e) v[e] += g.acc_in[(long long)m * g.N + n + e];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (e < nv) v[e] += g.acc_in[(long long)m * g.N + n + e];
                     }
                 }
                 if (g.bias) {
-                    for (int e = 0; e < nv; ++e) v[e] += h2f(g.bias[n + e]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < nv) v[e] += h2f(g.bias[n + e]);
                 }
                 if (g.relu) {
 #pragma unroll
@@ -284,7 +297,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
                         const uint2 raw = *reinterpret_cast<const uint2*>(ap);
                         t[0] = raw.x & 0xFFFF; t[1] = raw.x >> 16; t[2] = raw.y & 0xFFFF; t[3] = raw.y >> 16;
                     } else {
-                        for (int e = 0; e < nv; ++e) t[e] = ap[e];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (e < nv) t[e] = ap[e];
                     }
                     if (g.relu_src) {
 #pragma unroll
@@ -296,14 +311,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
                     }
                 }
                 if (g.found_inf) {
-                    for (int e = 0; e < nv; ++e) bad |= half_nonfinite(h[e]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) bad |= (e < nv) && half_nonfinite(h[e]);
                 }
                 uint16_t* dst = C + (long long)m * g.ldc + n;
                 if (nv == 4) {
                     *reinterpret_cast<uint2*>(dst) =
                         make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
                 } else {
-                    for (int e = 0; e < nv; ++e) dst[e] = h[e];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < nv) dst[e] = h[e];
                 }
             }
         }
