@@ -21,11 +21,14 @@
 
 #include <mutex>
 #include <cstring>
+#include <type_traits>
+#include <utility>
 
 namespace mp {
 
 constexpr int GEMM_THREADS = 256;
 constexpr int BK           = 64;  // halves per LDS row = 128 bytes = 8 slots of 16 bytes
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 struct GemmArgs {
     const uint16_t* A;
@@ -47,11 +50,21 @@ struct GemmArgs {
     int             tiles_m, tiles_n;
 };
 
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}).
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
 // 16-byte global load of 8 halves starting at p[0], of which only the first `valid` (0..8) exist.
-__device__ __forceinline__ uint4 load8_guard(const uint16_t* p, int valid) {
-    if (valid >= 8) return *reinterpret_cast<const uint4*>(p);
+__device__ __forceinline__ u32x4 load8_guard(const uint16_t* p, int valid) {
+    if (valid >= 8) return *reinterpret_cast<const u32x4*>(p);
     // ragged tail: element loads, assembled with compile-time indices only (no addressable local)
     unsigned w0 = 0, w1 = 0, w2 = 0, w3 = 0;
     if (valid > 0) w0 |= (unsigned)p[0];
@@ -62,65 +75,81 @@ __device__ __forceinline__ uint4 load8_guard(const uint16_t* p, int valid) {
     if (valid > 5) w2 |= (unsigned)p[5] << 16;
     if (valid > 6) w3 |= (unsigned)p[6];
     if (valid > 7) w3 |= (unsigned)p[7] << 16;
-    return make_uint4(w0, w1, w2, w3);
+    return u32x4{w0, w1, w2, w3};
 }
 
-// ---- global -> registers.  R = tile rows (BM or BN).  Up to 8 x 16 bytes per lane.
+// ---- global -> registers -> LDS.  R = tile rows (BM or BN).  Up to 8 x 16 bytes per lane.
+// Addresses are split into a wave-uniform part (tile origin, advanced per k-step; lives in scalar
+// registers) and a per-lane part computed once, so the k-loop carries almost no address arithmetic.
+// load<false> is straight-line code (no bounds tests) for tiles that lie fully inside the matrix
+// and the k-range; load<true> tests every access and zero-fills, and is only taken at the edges.
 template <int R>
-struct KCLoader {  // operand stored [row][k]
-    static constexpr int NV = (R * 8 + GEMM_THREADS - 1) / GEMM_THREADS;  // vectors per lane
-    uint4                v[NV];
-    __device__ __forceinline__ void load(const uint16_t* base, int ld, int row0, int rows, int k0, int kend) {
-        const int kv = threadIdx.x & 7;
-        const int k  = k0 + kv * 8;
+struct KCLoader {  // operand stored [row][k]; `tile` points at element (row0, k0)
+    static constexpr int NV = R / 32;  // vectors per lane (lane -> row tid/8 + 32 i, k-slot tid%8)
+    u32x4                v[NV];
+    unsigned             lane_off;     // elements from the tile origin
+    int                  lds_off[2];   // byte offset inside the LDS tile for even / odd i (before + i*4096)
+    __device__ __forceinline__ void init(int ld) {
+        const int r0 = threadIdx.x >> 3, kv = threadIdx.x & 7;
+        lane_off   = (unsigned)r0 * (unsigned)ld + kv * 8;
+        lds_off[0] = r0 * 128 + ((kv ^ swz(r0)) << 4);
+        lds_off[1] = r0 * 128 + ((kv ^ swz(r0) ^ 4) << 4);
+    }
+    template <bool GUARD>
+    __device__ __forceinline__ void load(const uint16_t* tile, int ld, int rows_left, int k_left) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            const int r   = (threadIdx.x >> 3) + 32 * i;
-            const int row = row0 + r;
-            if (r < R && row < rows)
-                v[i] = load8_guard(base + (long long)row * ld + k, kend - k);
-            else
-                v[i] = make_uint4(0, 0, 0, 0);
-        }
-    }
-    __device__ __forceinline__ void store(char* lds) const {
-        const int kv = threadIdx.x & 7;
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int r = (threadIdx.x >> 3) + 32 * i;
-            if (r < R) *reinterpret_cast<uint4*>(lds + r * 128 + ((kv ^ swz(r)) << 4)) = v[i];
-        }
-    }
-};
-
-template <int R>
-struct OCLoader {  // operand stored [k][row]: each active lane owns an 8(k) x 8(row) block
-    uint4                v[8];
-    __device__ __forceinline__ void load(const uint16_t* base, int ld, int row0, int rows, int k0, int kend) {
-        constexpr int G = R / 8;  // row groups
-        if ((int)threadIdx.x < R) {
-            const int rg = threadIdx.x % G, kg = threadIdx.x / G;
-            const int row = row0 + rg * 8;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int k = k0 + kg * 8 + j;
-                if (k < kend)
-                    v[j] = load8_guard(base + (long long)k * ld + row, rows - row);
-                else
-                    v[j] = make_uint4(0, 0, 0, 0);
+            const uint16_t* p = tile + (long long)(32 * i) * ld + lane_off;
+            if (GUARD) {
+                const int r = (threadIdx.x >> 3) + 32 * i;
+                v[i] = (r < rows_left) ? load8_guard(p, k_left - (int)(threadIdx.x & 7) * 8) : u32x4{0u, 0u, 0u, 0u};
+            } else {
+                v[i] = *reinterpret_cast<const u32x4*>(p);
             }
         }
     }
     __device__ __forceinline__ void store(char* lds) const {
-        constexpr int G = R / 8;
-        if ((int)threadIdx.x < R) {
-            const int      rg = threadIdx.x % G, kg = threadIdx.x / G;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) *reinterpret_cast<u32x4*>(lds + lds_off[i & 1] + i * 4096) = v[i];
+    }
+};
+
+template <int R>
+struct OCLoader {  // operand stored [k][row]; `tile` points at element (k0, row0).
+    // Each active lane owns an 8(k) x 8(row) block: row group rg = tid % (R/8), k group kg = tid / (R/8).
+    u32x4    v[8];
+    unsigned lane_off;
+    int      lds_base, lds_t;  // LDS row block base and swizzle term: slot(i) = (lds_t ^ i)
+    static constexpr int G = R / 8;
+    __device__ __forceinline__ bool active() const { return R >= GEMM_THREADS || (int)threadIdx.x < R; }
+    __device__ __forceinline__ void init(int ld) {
+        const int rg = threadIdx.x % G, kg = threadIdx.x / G;
+        lane_off = (unsigned)(kg * 8) * (unsigned)ld + rg * 8;
+        lds_base = rg * 8 * 128;
+        lds_t    = (kg ^ rg) & 7;  // swz(rg*8 + i) = (i ^ rg) & 7
+    }
+    template <bool GUARD>
+    __device__ __forceinline__ void load(const uint16_t* tile, int ld, int rows_left, int k_left) {
+        if (active()) {
+            const int rg = threadIdx.x % G, kg = threadIdx.x / G;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint16_t* p = tile + (long long)j * ld + lane_off;
+                if (GUARD)
+                    v[j] = (kg * 8 + j < k_left) ? load8_guard(p, rows_left - rg * 8) : u32x4{0u, 0u, 0u, 0u};
+                else
+                    v[j] = *reinterpret_cast<const u32x4*>(p);
+            }
+        }
+    }
+    __device__ __forceinline__ void store(char* lds) const {
+        if (active()) {
             const unsigned in[8][4] = {{v[0].x, v[0].y, v[0].z, v[0].w}, {v[1].x, v[1].y, v[1].z, v[1].w},
                                        {v[2].x, v[2].y, v[2].z, v[2].w}, {v[3].x, v[3].y, v[3].z, v[3].w},
                                        {v[4].x, v[4].y, v[4].z, v[4].w}, {v[5].x, v[5].y, v[5].z, v[5].w},
                                        {v[6].x, v[6].y, v[6].z, v[6].w}, {v[7].x, v[7].y, v[7].z, v[7].w}};
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {  // output row i of the block = column i of the loaded block
+            for (int i = 0; i < 8; ++i) {  // LDS row i of the block = column i of the loaded block
                 unsigned o[4];
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
@@ -128,8 +157,7 @@ struct OCLoader {  // operand stored [k][row]: each active lane owns an 8(k) x 8
                     const unsigned lo = in[2 * p][i >> 1], hi = in[2 * p + 1][i >> 1];
                     o[p] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                 }
-                const int r = rg * 8 + i;
-                *reinterpret_cast<uint4*>(lds + r * 128 + ((kg ^ swz(r)) << 4)) = make_uint4(o[0], o[1], o[2], o[3]);
+                *reinterpret_cast<u32x4*>(lds + lds_base + i * 128 + ((lds_t ^ i) << 4)) = u32x4{o[0], o[1], o[2], o[3]};
             }
         }
     }
@@ -140,11 +168,9 @@ struct LoaderSel { typedef KCLoader<R> T; };
 template <int R>
 struct LoaderSel<R, false> { typedef OCLoader<R> T; };
 
-__device__ __forceinline__ f16x8 lds_frag(const char* lds, int row, int kv) {
-    return *reinterpret_cast<const f16x8*>(lds + row * 128 + ((kv ^ swz(row)) << 4));
-}
-
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC>
+// EDGE = false: every tile lies fully inside the matrices and K is a multiple of BK, so neither the
+// loads nor the stores carry bounds tests.  EDGE = true: every access is tested (ragged shapes).
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool EDGE>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
     static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
@@ -190,36 +216,65 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
 
     typename LoaderSel<BM, A_KC>::T la;
     typename LoaderSel<BN, B_KC>::T lb;
+    la.init(g.lda);
+    lb.init(g.ldb);
+    // wave-uniform tile origins, advanced by one k-step per iteration
+    const uint16_t* ta = A_KC ? A + (long long)m0 * g.lda + kbeg : A + (long long)kbeg * g.lda + m0;
+    const uint16_t* tb = B_KC ? B + (long long)n0 * g.ldb + kbeg : B + (long long)kbeg * g.ldb + n0;
+    const long long step_a = A_KC ? BK : (long long)BK * g.lda;
+    const long long step_b = B_KC ? BK : (long long)BK * g.ldb;
 
-    if (nkt > 0) {
-        la.load(A, g.lda, m0, g.M, kbeg, kend);
-        lb.load(B, g.ldb, n0, g.N, kbeg, kend);
-        la.store(smem);
-        lb.store(smem + A_BYTES);
+    // matrix-core fragment addresses inside an LDS tile: row = base row + 32 i, k-slot = 2 kk + lane/32,
+    // swizzled; only four distinct per-lane offsets exist (the rest are immediates), see swz().
+    const int arow = wm * WM + (lane & 31), brow = wn * WN + (lane & 31);
+    int       offa[4], offb[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        offa[c] = arow * 128 + ((((2 * c) | (lane >> 5)) ^ swz(arow)) << 4);
+        offb[c] = brow * 128 + ((((2 * c) | (lane >> 5)) ^ swz(brow)) << 4);
     }
-    __syncthreads();
 
-    for (int kt = 0; kt < nkt; ++kt) {
-        const char* sa = smem + (kt & 1) * STAGE;
-        const char* sb = sa + A_BYTES;
-        const bool  more = kt + 1 < nkt;
+    // One copy of each phase keeps the kernel small enough for the instruction cache: iteration
+    // kt = -1 only stages the first tile; iteration kt loads tile kt+1 into registers, multiplies
+    // tile kt out of LDS, then stores tile kt+1 into the other LDS stage.
+    for (int kt = -1; kt < nkt; ++kt) {
+        const bool more = kt + 1 < nkt;
         if (more) {
-            la.load(A, g.lda, m0, g.M, kbeg + (kt + 1) * BK, kend);
-            lb.load(B, g.ldb, n0, g.N, kbeg + (kt + 1) * BK, kend);
+            const int k0 = kbeg + (kt + 1) * BK;
+            la.template load<EDGE>(ta, g.lda, g.M - m0, kend - k0);
+            lb.template load<EDGE>(tb, g.ldb, g.N - n0, kend - k0);
+            ta += step_a;
+            tb += step_b;
         }
+        if (kt >= 0) {
+            const char* sa = smem + (kt & 1) * STAGE;
+            const char* sb = sa + A_BYTES;
+            // fragments are double-buffered in registers: the LDS reads of k-slice kk+1 are issued
+            // before the matrix-core instructions of slice kk, whose run time covers their latency.
+            // The scheduling barriers keep the compiler from hoisting all four slices' reads at once
+            // (which would not fit the register file).
+            f16x8 af[2][TM], bf[2][TN];
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            f16x8     af[TM], bf[TN];
-            const int kv = kk * 2 + (lane >> 5);
+            for (int i = 0; i < TM; ++i) af[0][i] = *reinterpret_cast<const f16x8*>(sa + offa[(i & 1) << 1] + i * 4096);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = lds_frag(sa, wm * WM + i * 32 + (lane & 31), kv);
+            for (int j = 0; j < TN; ++j) bf[0][j] = *reinterpret_cast<const f16x8*>(sb + offb[(j & 1) << 1] + j * 4096);
+            static_for<BK / 16>([&](auto kc) {
+                constexpr int kk = decltype(kc)::value, cur = kk & 1, nxt = cur ^ 1;
+                if (kk + 1 < BK / 16) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = lds_frag(sb, wn * WN + j * 32 + (lane & 31), kv);
+                    for (int i = 0; i < TM; ++i)
+                        af[nxt][i] = *reinterpret_cast<const f16x8*>(sa + offa[(kk + 1) ^ ((i & 1) << 1)] + i * 4096);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                    for (int j = 0; j < TN; ++j)
+                        bf[nxt][j] = *reinterpret_cast<const f16x8*>(sb + offb[(kk + 1) ^ ((j & 1) << 1)] + j * 4096);
+                }
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[j], af[i], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            });
         }
         if (more) {
             char* da = smem + ((kt + 1) & 1) * STAGE;
@@ -229,103 +284,120 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
         __syncthreads();
     }
 
-    // ---- epilogue
+    // ---- epilogue.  Accumulators go through LDS (per wave, one 32-row slab at a time, fp32) so that
+    // global memory sees whole rows: each lane then owns 8 consecutive columns of one row and moves
+    // 16 bytes per access (bias, residual / ReLU-source loads and the fp16 store; 2 x 16 bytes for fp32).
     uint16_t*       C   = g.C ? g.C + bo * g.sc_o + bi * g.sc_i : nullptr;
     const uint16_t* aux = g.relu_src ? g.relu_src : g.add;
     if (aux) aux += bo * g.sc_o + bi * g.sc_i;
-    float* C32 = g.C32 ? g.C32 + (long long)blockIdx.z * g.M * g.N : nullptr;
-    bool   bad = false;
+    float*     C32   = g.C32 ? g.C32 + (long long)blockIdx.z * g.M * g.N : nullptr;
+    const bool split = gridDim.z > 1;
+    bool       bad   = false;
+
+    constexpr int SLD = WN + 4;                         // slab row stride in floats (pad: conflict-free)
+    float*        slab = reinterpret_cast<float*>(smem) + wave * (32 * SLD);
+    constexpr int LPR = WN / 8;                         // lanes per slab row
+    constexpr int RPP = 64 / LPR;                       // rows per pass
+    const int     lr = lane / LPR, lc = (lane % LPR) * 8;
+
+    static_for<TM>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        __syncthreads();  // previous slab fully read (and, first time, main-loop LDS reads done)
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * WM + i * 32 + (lane & 31);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * WN + j * 32 + q * 8 + (lane >> 5) * 4;
-                if (m >= g.M || n >= g.N) continue;
-                float     v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-                const int nv   = min(4, g.N - n);
-                if (C32) {  // raw accumulator out (split-K partial, or fp32 result with alpha and addend)
-                    float* dst = C32 + (long long)m * g.N + n;
-                    if (gridDim.z == 1) {
+                const f32x4 v = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+                *reinterpret_cast<f32x4*>(slab + (lane & 31) * SLD + j * 32 + q * 8 + (lane >> 5) * 4) = v;
+            }
+        __syncthreads();
+#pragma unroll 1
+        for (int ps = 0; ps < 32 / RPP; ++ps) {
+            const int r = ps * RPP + lr;
+            const int m = m0 + wm * WM + i * 32 + r;
+            const int n = n0 + wn * WN + lc;
+            if (EDGE && (m >= g.M || n >= g.N)) continue;
+            const f32x4 s0 = *reinterpret_cast<const f32x4*>(slab + r * SLD + lc);
+            const f32x4 s1 = *reinterpret_cast<const f32x4*>(slab + r * SLD + lc + 4);
+            float       v[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+            const bool  full = !EDGE || n + 8 <= g.N;
+            const long long mn = (long long)m * g.N + n;
+            if (C32) {  // raw accumulator out: split-K partial, or fp32 result with alpha and addend
+                if (!split) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] *= g.alpha;
-                        if (g.acc_in) {
+                    for (int e = 0; e < 8; ++e) v[e] *= g.alpha;
+                    if (g.acc_in) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (e < nv) v[e] += g.acc_in[(long long)m * g.N + n + e];
-                        }
-                    }
-                    if (nv == 4) {
-                        *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (e < nv) dst[e] = v[e];
-                    }
-                    continue;
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] *= g.alpha;
-                if (g.acc_in) {
-                    if (nv == 4) {
-                        const float4 t = *reinterpret_cast<const float4*>(g.acc_in + (long long)m * g.N + n);
-                        v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (e < nv) v[e] += g.acc_in[(long long)m * g.N + n + e];
+                        for (int e = 0; e < 8; ++e)
+                            if (full || n + e < g.N) v[e] += g.acc_in[mn + e];
                     }
                 }
-                if (g.bias) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (e < nv) v[e] += h2f(g.bias[n + e]);
-                }
-                if (g.relu) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-                }
-                uint16_t h[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = f2h(v[e]);
-                if (aux) {
-                    const uint16_t* ap = aux + (long long)m * g.ld_aux + n;
-                    uint16_t        t[4] = {0, 0, 0, 0};
-                    if (nv == 4) {
-                        const uint2 raw = *reinterpret_cast<const uint2*>(ap);
-                        t[0] = raw.x & 0xFFFF; t[1] = raw.x >> 16; t[2] = raw.y & 0xFFFF; t[3] = raw.y >> 16;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (e < nv) t[e] = ap[e];
-                    }
-                    if (g.relu_src) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (!(h2f(t[e]) > 0.f)) h[e] = 0;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) h[e] = f2h(h2f(h[e]) + h2f(t[e]));
-                    }
-                }
-                if (g.found_inf) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) bad |= (e < nv) && half_nonfinite(h[e]);
-                }
-                uint16_t* dst = C + (long long)m * g.ldc + n;
-                if (nv == 4) {
-                    *reinterpret_cast<uint2*>(dst) =
-                        make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
+                if (full) {
+                    *reinterpret_cast<float4*>(C32 + mn)     = make_float4(v[0], v[1], v[2], v[3]);
+                    *reinterpret_cast<float4*>(C32 + mn + 4) = make_float4(v[4], v[5], v[6], v[7]);
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (e < nv) dst[e] = h[e];
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < g.N) C32[mn + e] = v[e];
+                }
+                continue;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= g.alpha;
+            if (g.acc_in) {
+                if (full) {
+                    const float4 t0 = *reinterpret_cast<const float4*>(g.acc_in + mn);
+                    const float4 t1 = *reinterpret_cast<const float4*>(g.acc_in + mn + 4);
+                    v[0] += t0.x; v[1] += t0.y; v[2] += t0.z; v[3] += t0.w;
+                    v[4] += t1.x; v[5] += t1.y; v[6] += t1.z; v[7] += t1.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < g.N) v[e] += g.acc_in[mn + e];
                 }
             }
+            if (g.bias) {
+                const u32x4 braw = load8_guard(g.bias + n, g.N - n);
+                const unsigned bw[4] = {braw.x, braw.y, braw.z, braw.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += h2f((uint16_t)((e & 1) ? (bw[e >> 1] >> 16) : (bw[e >> 1] & 0xFFFF)));
+            }
+            if (g.relu) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+            }
+            uint16_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = f2h(v[e]);
+            if (aux) {
+                const u32x4 araw = load8_guard(aux + (long long)m * g.ld_aux + n, g.N - n);
+                const unsigned aw[4] = {araw.x, araw.y, araw.z, araw.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float t = h2f((uint16_t)((e & 1) ? (aw[e >> 1] >> 16) : (aw[e >> 1] & 0xFFFF)));
+                    if (g.relu_src) {
+                        if (!(t > 0.f)) h[e] = 0;
+                    } else {
+                        h[e] = f2h(h2f(h[e]) + t);
+                    }
+                }
+            }
+            if (g.found_inf) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bad |= (full || n + e < g.N) && half_nonfinite(h[e]);
+            }
+            uint16_t* dst = C + (long long)m * g.ldc + n;
+            if (full) {
+                *reinterpret_cast<uint4*>(dst) =
+                    make_uint4((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
+                               (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < g.N) dst[e] = h[e];
+            }
         }
-    }
+    });
     if (g.found_inf && __any(bad)) {
         if (lane == 0) atomicOr(g.found_inf, 1);
     }
@@ -403,19 +475,26 @@ static const TileCfg kTiles[] = {{256, 256, 1.00f}, {256, 128, 0.85f}, {128, 256
 constexpr int   kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int   kCUs      = 256;
 
-template <int BM, int BN, int WM_, int WN_, bool AKC, bool BKC>
-static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t hs) {
+template <int BM, int BN, int WM_, int WN_, bool AKC, bool BKC, bool EDGE>
+static int launch_variant(const GemmArgs& g, dim3 grid, hipStream_t hs) {
     constexpr size_t  lds = 2 * (size_t)(BM + BN) * 128;
     static std::once_flag once;
     static hipError_t     attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WM_, WN_, AKC, BKC>),
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WM_, WN_, AKC, BKC, EDGE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     if (attr_err != hipSuccess) return hip_fail(attr_err, "gemm: hipFuncSetAttribute(LDS size)");
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM_, WN_, AKC, BKC>), grid, dim3(GEMM_THREADS), lds, hs, g);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM_, WN_, AKC, BKC, EDGE>), grid, dim3(GEMM_THREADS), lds, hs, g);
     MP_LAUNCH_CHECK("gemm launch");
     return MP_OK;
+}
+
+template <int BM, int BN, int WM_, int WN_, bool AKC, bool BKC>
+static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t hs) {
+    const bool edge = (g.M % BM) != 0 || (g.N % BN) != 0 || (g.K % BK) != 0;
+    return edge ? launch_variant<BM, BN, WM_, WN_, AKC, BKC, true>(g, grid, hs)
+                : launch_variant<BM, BN, WM_, WN_, AKC, BKC, false>(g, grid, hs);
 }
 
 template <bool AKC, bool BKC>
