@@ -20,6 +20,7 @@
 #include "common.hpp"
 
 #include <mutex>
+#include <cstdlib>
 #include <cstring>
 #include <type_traits>
 #include <utility>
@@ -86,6 +87,7 @@ __device__ __forceinline__ u32x4 load8_guard(const uint16_t* p, int valid) {
 template <int R>
 struct KCLoader {  // operand stored [row][k]; `tile` points at element (row0, k0)
     static constexpr int NV = R / 32;  // vectors per lane (lane -> row tid/8 + 32 i, k-slot tid%8)
+    static constexpr int N_LOADS = NV;
     u32x4                v[NV];
     unsigned             lane_off;     // elements from the tile origin
     int                  lds_off[2];   // byte offset inside the LDS tile for even / odd i (before + i*4096)
@@ -95,71 +97,89 @@ struct KCLoader {  // operand stored [row][k]; `tile` points at element (row0, k
         lds_off[0] = r0 * 128 + ((kv ^ swz(r0)) << 4);
         lds_off[1] = r0 * 128 + ((kv ^ swz(r0) ^ 4) << 4);
     }
-    template <bool GUARD>
-    __device__ __forceinline__ void load(const uint16_t* tile, int ld, int rows_left, int k_left) {
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const uint16_t* p = tile + (long long)(32 * i) * ld + lane_off;
-            if (GUARD) {
-                const int r = (threadIdx.x >> 3) + 32 * i;
-                v[i] = (r < rows_left) ? load8_guard(p, k_left - (int)(threadIdx.x & 7) * 8) : u32x4{0u, 0u, 0u, 0u};
-            } else {
-                v[i] = *reinterpret_cast<const u32x4*>(p);
-            }
+    template <bool GUARD, int I>
+    __device__ __forceinline__ void load_one(const uint16_t* tile, int ld, int rows_left, int k_left) {
+        const uint16_t* p = tile + (long long)(32 * I) * ld + lane_off;
+        if (GUARD) {
+            const int r = (threadIdx.x >> 3) + 32 * I;
+            v[I] = (r < rows_left) ? load8_guard(p, k_left - (int)(threadIdx.x & 7) * 8) : u32x4{0u, 0u, 0u, 0u};
+        } else {
+            v[I] = *reinterpret_cast<const u32x4*>(p);
         }
     }
+    template <int I>
+    __device__ __forceinline__ void store_one(char* lds) const {
+        *reinterpret_cast<u32x4*>(lds + lds_off[I & 1] + I * 4096) = v[I];
+    }
+    template <bool GUARD>
+    __device__ __forceinline__ void load(const uint16_t* tile, int ld, int rows_left, int k_left) {
+        static_for<NV>([&](auto ic) { load_one<GUARD, decltype(ic)::value>(tile, ld, rows_left, k_left); });
+    }
     __device__ __forceinline__ void store(char* lds) const {
-#pragma unroll
-        for (int i = 0; i < NV; ++i) *reinterpret_cast<u32x4*>(lds + lds_off[i & 1] + i * 4096) = v[i];
+        static_for<NV>([&](auto ic) { store_one<decltype(ic)::value>(lds); });
     }
 };
 
 template <int R>
 struct OCLoader {  // operand stored [k][row]; `tile` points at element (k0, row0).
-    // Each active lane owns an 8(k) x 8(row) block: row group rg = tid % (R/8), k group kg = tid / (R/8).
-    u32x4    v[8];
+    // Every lane owns a KB(k) x 8(row) block of the 64 x R tile, KB = R/32 (8 for R = 256): row group
+    // rg = tid % (R/8), k group kg = tid / (R/8).  The block is transposed in registers with byte
+    // permutes and written to LDS as 8 row pieces of KB halves.
+    static constexpr int G = R / 8, KB = R / 32;
+    static constexpr int N_LOADS = KB;
+    u32x4    v[KB];
     unsigned lane_off;
-    int      lds_base, lds_t;  // LDS row block base and swizzle term: slot(i) = (lds_t ^ i)
-    static constexpr int G = R / 8;
-    __device__ __forceinline__ bool active() const { return R >= GEMM_THREADS || (int)threadIdx.x < R; }
+    int      lds_row0;  // byte offset of (row rg*8, k kg*KB) before the slot swizzle: row*128 + within-slot bytes
+    int      lds_slot;  // (slot of k = kg*KB) ^ (rg & 7); slot(i) = lds_slot ^ i   [swz(rg*8 + i) = (i ^ rg) & 7]
     __device__ __forceinline__ void init(int ld) {
         const int rg = threadIdx.x % G, kg = threadIdx.x / G;
-        lane_off = (unsigned)(kg * 8) * (unsigned)ld + rg * 8;
-        lds_base = rg * 8 * 128;
-        lds_t    = (kg ^ rg) & 7;  // swz(rg*8 + i) = (i ^ rg) & 7
+        const int k  = kg * KB;
+        lane_off = (unsigned)k * (unsigned)ld + rg * 8;
+        lds_row0 = rg * 8 * 128 + (k & 7) * 2;
+        lds_slot = ((k >> 3) ^ rg) & 7;
+    }
+    template <bool GUARD, int J>
+    __device__ __forceinline__ void load_one(const uint16_t* tile, int ld, int rows_left, int k_left) {
+        const uint16_t* p = tile + (long long)J * ld + lane_off;
+        if (GUARD) {
+            const int rg = threadIdx.x % G, kg = threadIdx.x / G;
+            v[J] = (kg * KB + J < k_left) ? load8_guard(p, rows_left - rg * 8) : u32x4{0u, 0u, 0u, 0u};
+        } else {
+            v[J] = *reinterpret_cast<const u32x4*>(p);
+        }
+    }
+    // half (k = j, row I) of the block is the low or high half of word I/2 of v[j]
+    template <int I>
+    __device__ __forceinline__ unsigned pair(int j0) const {
+        const unsigned lo = v[j0][I >> 1], hi = v[j0 + 1][I >> 1];
+        return (I & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+    }
+    template <int I>
+    __device__ __forceinline__ void store_row(char* lds) const {
+        char* dst = lds + lds_row0 + I * 128 + ((lds_slot ^ I) << 4);
+        if constexpr (KB == 8) {
+            *reinterpret_cast<u32x4*>(dst) = u32x4{pair<I>(0), pair<I>(2), pair<I>(4), pair<I>(6)};
+        } else if constexpr (KB == 4) {
+            typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+            *reinterpret_cast<u32x2*>(dst) = u32x2{pair<I>(0), pair<I>(2)};
+        } else if constexpr (KB == 2) {
+            *reinterpret_cast<unsigned*>(dst) = pair<I>(0);
+        } else {
+            const unsigned w = v[0][I >> 1];
+            *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((I & 1) ? (w >> 16) : (w & 0xFFFFu));
+        }
+    }
+    // store item J of KB covers 8/KB of the block's 8 LDS rows, so that items and loads pair up 1:1
+    template <int J>
+    __device__ __forceinline__ void store_one(char* lds) const {
+        static_for<8 / KB>([&](auto rc) { store_row<J*(8 / KB) + decltype(rc)::value>(lds); });
     }
     template <bool GUARD>
     __device__ __forceinline__ void load(const uint16_t* tile, int ld, int rows_left, int k_left) {
-        if (active()) {
-            const int rg = threadIdx.x % G, kg = threadIdx.x / G;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint16_t* p = tile + (long long)j * ld + lane_off;
-                if (GUARD)
-                    v[j] = (kg * 8 + j < k_left) ? load8_guard(p, rows_left - rg * 8) : u32x4{0u, 0u, 0u, 0u};
-                else
-                    v[j] = *reinterpret_cast<const u32x4*>(p);
-            }
-        }
+        static_for<KB>([&](auto jc) { load_one<GUARD, decltype(jc)::value>(tile, ld, rows_left, k_left); });
     }
     __device__ __forceinline__ void store(char* lds) const {
-        if (active()) {
-            const unsigned in[8][4] = {{v[0].x, v[0].y, v[0].z, v[0].w}, {v[1].x, v[1].y, v[1].z, v[1].w},
-                                       {v[2].x, v[2].y, v[2].z, v[2].w}, {v[3].x, v[3].y, v[3].z, v[3].w},
-                                       {v[4].x, v[4].y, v[4].z, v[4].w}, {v[5].x, v[5].y, v[5].z, v[5].w},
-                                       {v[6].x, v[6].y, v[6].z, v[6].w}, {v[7].x, v[7].y, v[7].z, v[7].w}};
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {  // LDS row i of the block = column i of the loaded block
-                unsigned o[4];
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    // halves (k = 2p, row i) and (k = 2p+1, row i): low or high half of word i/2
-                    const unsigned lo = in[2 * p][i >> 1], hi = in[2 * p + 1][i >> 1];
-                    o[p] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                }
-                *reinterpret_cast<u32x4*>(lds + lds_base + i * 128 + ((lds_t ^ i) << 4)) = u32x4{o[0], o[1], o[2], o[3]};
-            }
-        }
+        static_for<KB>([&](auto jc) { store_one<decltype(jc)::value>(lds); });
     }
 };
 
@@ -214,15 +234,22 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    typename LoaderSel<BM, A_KC>::T la;
-    typename LoaderSel<BN, B_KC>::T lb;
-    la.init(g.lda);
-    lb.init(g.ldb);
-    // wave-uniform tile origins, advanced by one k-step per iteration
+    // Two register sets per operand: the global loads of k-tile t+2 are issued before the matrix-core
+    // work of tile t and are first needed (for the LDS store) after the work of tile t+1, so a load has
+    // two compute phases to arrive.  With one workgroup per CU and one wave per SIMD nothing else hides
+    // the memory latency.
+    typename LoaderSel<BM, A_KC>::T la0, la1;
+    typename LoaderSel<BN, B_KC>::T lb0, lb1;
+    la0.init(g.lda);
+    la1.init(g.lda);
+    lb0.init(g.ldb);
+    lb1.init(g.ldb);
+    // wave-uniform tile origins, advanced by one k-step per load
     const uint16_t* ta = A_KC ? A + (long long)m0 * g.lda + kbeg : A + (long long)kbeg * g.lda + m0;
     const uint16_t* tb = B_KC ? B + (long long)n0 * g.ldb + kbeg : B + (long long)kbeg * g.ldb + n0;
     const long long step_a = A_KC ? BK : (long long)BK * g.lda;
     const long long step_b = B_KC ? BK : (long long)BK * g.ldb;
+    int             k_next = kbeg;  // first k of the next tile to load
 
     // matrix-core fragment addresses inside an LDS tile: row = base row + 32 i, k-slot = 2 kk + lane/32,
     // swizzled; only four distinct per-lane offsets exist (the rest are immediates), see swz().
@@ -234,55 +261,94 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
         offb[c] = brow * 128 + ((((2 * c) | (lane >> 5)) ^ swz(brow)) << 4);
     }
 
-    // One copy of each phase keeps the kernel small enough for the instruction cache: iteration
-    // kt = -1 only stages the first tile; iteration kt loads tile kt+1 into registers, multiplies
-    // tile kt out of LDS, then stores tile kt+1 into the other LDS stage.
-    for (int kt = -1; kt < nkt; ++kt) {
-        const bool more = kt + 1 < nkt;
-        if (more) {
-            const int k0 = kbeg + (kt + 1) * BK;
-            la.template load<EDGE>(ta, g.lda, g.M - m0, kend - k0);
-            lb.template load<EDGE>(tb, g.ldb, g.N - n0, kend - k0);
-            ta += step_a;
-            tb += step_b;
-        }
-        if (kt >= 0) {
-            const char* sa = smem + (kt & 1) * STAGE;
-            const char* sb = sa + A_BYTES;
-            // fragments are double-buffered in registers: the LDS reads of k-slice kk+1 are issued
-            // before the matrix-core instructions of slice kk, whose run time covers their latency.
-            // The scheduling barriers keep the compiler from hoisting all four slices' reads at once
-            // (which would not fit the register file).
-            f16x8 af[2][TM], bf[2][TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[0][i] = *reinterpret_cast<const f16x8*>(sa + offa[(i & 1) << 1] + i * 4096);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bf[0][j] = *reinterpret_cast<const f16x8*>(sb + offb[(j & 1) << 1] + j * 4096);
-            static_for<BK / 16>([&](auto kc) {
-                constexpr int kk = decltype(kc)::value, cur = kk & 1, nxt = cur ^ 1;
-                if (kk + 1 < BK / 16) {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-                        af[nxt][i] = *reinterpret_cast<const f16x8*>(sa + offa[(kk + 1) ^ ((i & 1) << 1)] + i * 4096);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        bf[nxt][j] = *reinterpret_cast<const f16x8*>(sb + offb[(kk + 1) ^ ((j & 1) << 1)] + j * 4096);
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        }
-        if (more) {
-            char* da = smem + ((kt + 1) & 1) * STAGE;
-            la.store(da);
-            lb.store(da + A_BYTES);
-        }
+    // Loads never branch in the interior variant: past the last k-tile the origin simply stops
+    // advancing, so the (unused) extra loads re-read the last tile and stay in bounds.
+    const int k_last = kbeg + (nkt > 0 ? nkt - 1 : 0) * BK;
+    auto load_next = [&](auto& la, auto& lb) {
+        la.template load<EDGE>(ta, g.lda, g.M - m0, kend - k_next);
+        lb.template load<EDGE>(tb, g.ldb, g.N - n0, kend - k_next);
+        const bool adv = k_next < k_last;
+        ta += adv ? step_a : 0;
+        tb += adv ? step_b : 0;
+        k_next += adv ? BK : 0;
+    };
+    // One pipeline step: issue the global loads of a later tile into (ln_a, ln_b), multiply the tile in
+    // LDS stage `sa` and store the tile held in (st_a, st_b) into LDS stage `da`.  In the interior
+    // variant this is one basic block, and the scheduling directives at its end interleave the memory
+    // instructions with the matrix-core instructions (which run 8 passes each and leave the issue
+    // port free): next-slice fragment reads right behind the first MFMAs of a slice, global loads
+    // and LDS stores spread evenly over the whole step.
+    auto step = [&](auto& ln_a, auto& ln_b, const auto& st_a, const auto& st_b, const char* sa, char* da) {
+        const char* sb = sa + A_BYTES;
+        constexpr int KS = BK / 16;                                // k-slices per tile
+        constexpr int MS = TM * TN;                                // matrix-core instructions per slice
+        constexpr int NM = MS * KS;                                // ... per step
+        constexpr int NR = TM + TN;                                // fragment reads per slice
+        constexpr int NA = LoaderSel<BM, A_KC>::T::N_LOADS, NB_ = LoaderSel<BN, B_KC>::T::N_LOADS;
+        constexpr int NG = NA + NB_;                               // global loads = LDS stores per step
+        constexpr int RPM = (NR + MS - 1) / MS;                    // fragment reads issued behind one MFMA
+        f16x8 af[2][TM], bf[2][TN];
+        // fragment f of slice kk into buffer kk&1 (f < TM: A rows, else B rows)
+        auto read_frag = [&](auto kkc, auto fc) {
+            constexpr int kk = decltype(kkc)::value, f = decltype(fc)::value;
+            if constexpr (f < TM)
+                af[kk & 1][f] = *reinterpret_cast<const f16x8*>(sa + offa[kk ^ ((f & 1) << 1)] + f * 4096);
+            else
+                bf[kk & 1][f - TM] = *reinterpret_cast<const f16x8*>(sb + offb[kk ^ (((f - TM) & 1) << 1)] + (f - TM) * 4096);
+        };
+        const int rows_a = g.M - m0, rows_b = g.N - n0, k_left = kend - k_next;
+        auto gload = [&](auto gc) {
+            constexpr int i = decltype(gc)::value;
+            if constexpr (i < NA) ln_a.template load_one<EDGE, i>(ta, g.lda, rows_a, k_left);
+            else ln_b.template load_one<EDGE, i - NA>(tb, g.ldb, rows_b, k_left);
+        };
+        auto lstore = [&](auto gc) {
+            constexpr int i = decltype(gc)::value;
+            if constexpr (i < NA) st_a.template store_one<i>(da);
+            else st_b.template store_one<i - NA>(da + A_BYTES);
+        };
+        static_for<NR>([&](auto fc) { read_frag(std::integral_constant<int, 0>{}, fc); });
+        __builtin_amdgcn_sched_barrier(0);
+        // Hand-placed order, pinned by scheduling barriers: behind matrix-core instruction m go the next
+        // slice's fragment reads (at the start of a slice) and an even share of the step's global loads
+        // and LDS stores.  An MFMA runs 8 passes and leaves the issue port free, so these overlap it.
+        static_for<NM>([&](auto mc) {
+            constexpr int m = decltype(mc)::value, kk = m / MS, q = m % MS, i = q / TN, j = q % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+            if constexpr (kk + 1 < KS) {
+                static_for<RPM>([&](auto rc) {
+                    constexpr int f = q * RPM + decltype(rc)::value;
+                    if constexpr (f < NR) read_frag(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, f>{});
+                });
+            }
+            constexpr int g0 = m * NG / NM, g1 = (m + 1) * NG / NM;
+            static_for<g1 - g0>([&](auto gc) { gload(std::integral_constant<int, g0 + decltype(gc)::value>{}); });
+            static_for<g1 - g0>([&](auto gc) { lstore(std::integral_constant<int, g0 + decltype(gc)::value>{}); });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        const bool adv = k_next < k_last;
+        ta += adv ? step_a : 0;
+        tb += adv ? step_b : 0;
+        k_next += adv ? BK : 0;
         __syncthreads();
+    };
+
+    // prologue: tiles 0 and 1 into the two register sets, tile 0 on into LDS stage 0
+    load_next(la0, lb0);
+    load_next(la1, lb1);
+    la0.store(smem);
+    lb0.store(smem + A_BYTES);
+    __syncthreads();
+    // step kt multiplies tile kt out of stage kt&1, stores tile kt+1 (loaded one step earlier) into the
+    // other stage and loads tile kt+2 into the register set tile kt came from.  Unrolled by two so that
+    // the register sets have static names.  Loads and stores past the last tile are redundant but
+    // harmless (see load_next; the extra LDS store goes to the stage nobody reads any more).
+    int kt = 0;
+    for (; kt + 1 < nkt; kt += 2) {
+        step(la0, lb0, la1, lb1, smem, smem + STAGE);
+        step(la1, lb1, la0, lb0, smem + STAGE, smem);
     }
+    if (kt < nkt) step(la0, lb0, la1, lb1, smem, smem + STAGE);  // odd tile count
 
     // ---- epilogue.  Accumulators go through LDS (per wave, one 32-row slab at a time, fp32) so that
     // global memory sees whole rows: each lane then owns 8 consecutive columns of one row and moves
@@ -518,6 +584,16 @@ struct Plan {
 // Pick the tile shape (and split count when allowed) that minimises an estimate of run time:
 // rounds of 256 workgroups x work per workgroup / shape efficiency.
 static Plan make_plan(int M, int N, int K, long long batches, bool allow_split) {
+    // tuning aid: MP_GEMM_TILE=<index into kTiles> forces a tile shape, MP_GEMM_SPLITS=<n> a split count
+    static const char* force_tile  = getenv("MP_GEMM_TILE");
+    static const char* force_split = getenv("MP_GEMM_SPLITS");
+    if (force_tile) {
+        int t = atoi(force_tile), sp = (force_split && allow_split) ? atoi(force_split) : 1;
+        if (t < 0 || t >= kNumTiles) t = 0;
+        if (sp < 1) sp = 1;
+        const int kps = ((K + sp - 1) / sp + BK - 1) / BK * BK;
+        return Plan{t, sp, kps > 0 ? kps : BK};
+    }
     Plan   best{0, 1, 0};
     double best_cost = 1e300;
     for (int t = 0; t < kNumTiles; ++t) {
@@ -558,7 +634,7 @@ static bool fast_path_ok(const GemmArgs& g) {
 static int run_gemm(GemmArgs g, bool a_kc, bool b_kc, long long batches, bool allow_split, float* ws, size_t ws_floats,
                     hipStream_t hs) {
     if (g.M == 0 || g.N == 0 || batches == 0) return MP_OK;
-    if (!fast_path_ok(g) || batches > 65535) {
+    if (!fast_path_ok(g) || batches > 65535 || g.K == 0) {
         if (batches > 65535) {
             set_error("gemm: more than 65535 batches");
             return MP_E_UNSUPPORTED;
