@@ -26,16 +26,26 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
 }
 
 // --------------------------------------------------------------------------- partial-sum finish
-// out16[c] = RNE16( sum_p part[p * stride + c] ), p ascending; optional non-finite flag.
+// out16[c] = RNE16( sum_p part[p * stride + c] ) in a fixed order; optional non-finite flag.
+// Workgroup = 32 columns x 8 part-lanes: lane q sums parts q, q+8, ... ; the 8 lane sums are then
+// added in lane order.
 __global__ __launch_bounds__(GL_THREADS) void finish_colsum_kernel(const float* __restrict__ part, int nparts,
                                                                    long long stride, int n, uint16_t* __restrict__ out16,
                                                                    mp_scale_state* st) {
-    const int c   = blockIdx.x * GL_THREADS + threadIdx.x;
-    bool      bad = false;
-    if (c < n) {
-        float acc = 0.f;
-        for (int p = 0; p < nparts; ++p) acc += part[(long long)p * stride + c];
-        const uint16_t h = f2h(acc);
+    __shared__ float sm[8][33];
+    const int cl = threadIdx.x & 31, q = threadIdx.x >> 5;
+    const int c  = blockIdx.x * 32 + cl;
+    float     acc = 0.f;
+    if (c < n)
+        for (int p = q; p < nparts; p += 8) acc += part[(long long)p * stride + c];
+    sm[q][cl] = acc;
+    __syncthreads();
+    bool bad = false;
+    if (q == 0 && c < n) {
+        float t = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t += sm[j][cl];
+        const uint16_t h = f2h(t);
         out16[c]         = h;
         bad              = half_nonfinite(h);
     }
@@ -45,20 +55,21 @@ __global__ __launch_bounds__(GL_THREADS) void finish_colsum_kernel(const float* 
 }
 
 // --------------------------------------------------------------------------- column sums
-// Workgroup = 32 column-groups x 8 row-lanes; VEC columns per column-group.
+// Workgroup = 8 column-groups x 32 row-lanes; VEC columns per column-group (a row piece of 8 x 16 B =
+// one 128-byte line per row when VEC = 8).
 template <int VEC>
 __global__ __launch_bounds__(GL_THREADS) void colsum_kernel(int rows, int cols, int ld, const uint16_t* __restrict__ dy,
                                                             int rows_per_block, float* __restrict__ part) {
-    __shared__ float sm[8][32 * VEC + 1];
-    const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;
-    const int c0 = (blockIdx.x * 32 + cg) * VEC;
+    __shared__ float sm[32][8 * VEC + 1];
+    const int cg = threadIdx.x & 7, rl = threadIdx.x >> 3;
+    const int c0 = (blockIdx.x * 8 + cg) * VEC;
     const int r0 = blockIdx.y * rows_per_block;
     const int r1 = min(rows, r0 + rows_per_block);
     float     acc[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) acc[k] = 0.f;
     if (c0 < cols) {
-        for (int r = r0 + rl; r < r1; r += 8) {
+        for (int r = r0 + rl; r < r1; r += 32) {
             if (VEC == 8) {
                 float f[8];
                 unpack8(*reinterpret_cast<const uint4*>(dy + (long long)r * ld + c0), f);
@@ -72,11 +83,11 @@ __global__ __launch_bounds__(GL_THREADS) void colsum_kernel(int rows, int cols, 
 #pragma unroll
     for (int k = 0; k < VEC; ++k) sm[rl][cg * VEC + k] = acc[k];
     __syncthreads();
-    for (int c = threadIdx.x; c < 32 * VEC; c += GL_THREADS) {
+    for (int c = threadIdx.x; c < 8 * VEC; c += GL_THREADS) {
         float t = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) t += sm[j][c];
-        const int gc = blockIdx.x * 32 * VEC + c;
+        for (int j = 0; j < 32; ++j) t += sm[j][c];
+        const int gc = blockIdx.x * 8 * VEC + c;
         if (gc < cols) part[(long long)blockIdx.y * cols + gc] = t;
     }
 }
@@ -431,9 +442,9 @@ static int grid_for(size_t units, int per_block, int cap) {
 
 // ---- column sums
 static int colsum_row_blocks(int rows, int cols, int vec) {
-    const int col_blocks = (cols + 32 * vec - 1) / (32 * vec);
+    const int col_blocks = (cols + 8 * vec - 1) / (8 * vec);
     int       rb         = 1024 / (col_blocks > 0 ? col_blocks : 1);
-    if (rb < 1) rb = 1;
+    if (rb > 32) rb = 32;                 // partial rows the finish kernel has to add up
     const int max_rb = (rows + 63) / 64;  // at least 64 rows per workgroup
     if (rb > max_rb) rb = max_rb;
     if (rb < 1) rb = 1;
@@ -459,7 +470,7 @@ extern "C" int mp_colsum(int rows, int cols, const mp_half* dY, int ld, mp_half*
     const int   V   = vec ? 8 : 1;
     const int   rb  = colsum_row_blocks(rows, cols, V);
     const int   rpb = (rows + rb - 1) / rb;
-    const dim3  grid((cols + 32 * V - 1) / (32 * V), rb);
+    const dim3  grid((cols + 8 * V - 1) / (8 * V), rb);
     float*      part = static_cast<float*>(ws);
     hipStream_t hs   = as_stream(stream);
     if (vec)
@@ -467,7 +478,7 @@ extern "C" int mp_colsum(int rows, int cols, const mp_half* dY, int ld, mp_half*
     else
         hipLaunchKernelGGL(colsum_kernel<1>, grid, dim3(GL_THREADS), 0, hs, rows, cols, ld, dY, rpb, part);
     MP_LAUNCH_CHECK("mp_colsum");
-    hipLaunchKernelGGL(finish_colsum_kernel, dim3((cols + GL_THREADS - 1) / GL_THREADS), dim3(GL_THREADS), 0, hs, part, rb,
+    hipLaunchKernelGGL(finish_colsum_kernel, dim3((cols + 31) / 32), dim3(GL_THREADS), 0, hs, part, rb,
                        (long long)cols, cols, db, st);
     MP_LAUNCH_CHECK("mp_colsum(finish)");
     return MP_OK;
@@ -526,7 +537,7 @@ extern "C" int mp_layernorm_bwd(int rows, int d, const mp_half* dy, const mp_hal
     hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(nb), dim3(GL_THREADS), (size_t)GL_WAVES * 2 * d * sizeof(float), hs, rows, d,
                        dy, x, a, gamma, mean, rstd, dz, part);
     MP_LAUNCH_CHECK("mp_layernorm_bwd");
-    const int fb = (d + GL_THREADS - 1) / GL_THREADS;
+    const int fb = (d + 31) / 32;
     hipLaunchKernelGGL(finish_colsum_kernel, dim3(fb), dim3(GL_THREADS), 0, hs, part, nb, (long long)2 * d, d, dgamma, st);
     MP_LAUNCH_CHECK("mp_layernorm_bwd(dgamma)");
     hipLaunchKernelGGL(finish_colsum_kernel, dim3(fb), dim3(GL_THREADS), 0, hs, part + d, nb, (long long)2 * d, d, dbeta, st);
