@@ -166,7 +166,7 @@ def test_config1_free_running_sequence_and_masters():
 
 
 # ------------------------------------------------------------------ configs 2, 3
-def op_level_transformer(step, wl, batch, tol=GRAD_TOL):
+def op_level_transformer(step, wl, batch, tol=GRAD_TOL, layers=None):
     """One forward/backward on the GPU with every stored tensor captured; each operation of the oracle is then
     evaluated on the GPU's own inputs of that operation and compared with the GPU's output of it."""
     tr = {}
@@ -191,9 +191,13 @@ def op_level_transformer(step, wl, batch, tol=GRAD_TOL):
     x = np32(step.x0)
     xs = []
     alpha = np.float32(1.0 / np.sqrt(d // h))
+    layers = tuple(range(wl.n_layers)) if layers is None else tuple(layers)
     for l in range(wl.n_layers):
         a, p = acts[l], f"l{l}."
         xs.append(x)
+        if l not in layers:
+            x = a["y2"]
+            continue
         check(a["qkv"], L.linear_fwd(MIXED, x, w[p + "wqkv"], w[p + "bqkv"]), f"{l} qkv")
         q, k, v = heads(a["qkv"])
         check(tr[("s", l)], MIXED.store(alpha * (q @ k.transpose(0, 1, 3, 2))), f"{l} scores")
@@ -212,6 +216,8 @@ def op_level_transformer(step, wl, batch, tol=GRAD_TOL):
     assert abs(float(step.loss) - float(loss_ref)) <= 1e-5 * float(loss_ref)
     check(tr[("dy2", wl.n_layers - 1)], dy_ref, "seed gradient")
     for l in range(wl.n_layers - 1, -1, -1):
+        if l not in layers:
+            continue
         a, p, x = acts[l], f"l{l}.", xs[l]
         _, c2 = L.layernorm_fwd(MIXED, a["y1"], a["g"], w[p + "ln2_g"], w[p + "ln2_b"])
         dz2, dg, db = L.layernorm_bwd(MIXED, tr[("dy2", l)], c2, w[p + "ln2_g"])
@@ -317,3 +323,143 @@ def test_config5_reduced_size():
     step2 = St.LSTMStep(wl)
     step2.set_batch(batch)
     free_running(step2, wl, f, batch, wl.steps)
+
+
+# ------------------------------------------------------------------ full sizes, in the configuration bench.py times
+def _graph_step(step):
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step.step()
+    return g
+
+
+def test_config3_full_size_bench_configuration():
+    """Config 3 at full size exactly as bench.py launches it (producer-side overflow inspection, one flat update
+    descriptor, HIP-graph replay): every operation of the first and last layer checked in situ against the oracle,
+    then graph replays against eager execution, bit for bit."""
+    wl = I.C3
+    batch = wl.batch()
+    step = St.TransformerStep(wl, prechecked=True, flat_update=True)
+    step.set_batch(batch)
+    worst = op_level_transformer(step, wl, batch, layers=(0, wl.n_layers - 1))
+    print(f"config 3 full size: worst in-situ op error {worst:.2e}")
+    # the optimizer wrapper at 75.6 M parameters against the oracle on the GPU's own gradients
+    before = _snapshot(step)
+    s0 = step.state()
+    g_gpu = {n: np32(step.P.g16[n]) for n in step.P.names}
+    step.optimizer()
+    after = _snapshot(step)
+    ost = O.ScaleState(scale=float(s0.scale), growth_interval=s0.growth_interval, opt_step=s0.opt_step)
+    for n in ("l0.wqkv", "l3.w1", "l5.w2", "l5.ln2_g", "l2.b1"):
+        t = [dict(g16=g_gpu[n], w32=before["w32"][n].copy(), w16=before["w16"][n].copy(), m=before["m"][n].copy(), v=before["v"][n].copy())]
+        assert O.unscale_check_update(MIXED, t, wl.opt, ost) == 0
+        assert rel_fro(after["w32"][n], t[0]["w32"]) <= MASTER_TOL and rel_fro(after["m"][n], t[0]["m"]) <= MASTER_TOL
+        assert np.array_equal(half_bits(after["w16"][n]), half_bits(MIXED.store(after["w32"][n])))
+    # graph replay == eager, several replays with eager work and synchronisation between them
+    eager = St.TransformerStep(wl, prechecked=True, flat_update=True)
+    eager.set_batch(batch)
+    eager.step()
+    graph = _graph_step(step)                     # capture = step 2 is recorded, not run
+    for _ in range(3):
+        graph.replay()
+        eager.step()
+        torch.cuda.synchronize()
+        assert float(step.loss) == float(eager.loss)
+        assert torch.equal(step.P.w32_arena, eager.P.w32_arena) and torch.equal(step.P.w16_arena, eager.P.w16_arena)
+    s = step.state()
+    assert (s.opt_step, s.skipped_steps, s.scale) == (4, 0, 2.0 ** 15)
+
+
+def test_config3_full_size_scale_sequence_over_growth_interval():
+    """120 iterations on the GPU; the recorded overflow flags replayed through the oracle's state machine must give
+    the recorded scale sequence (growth at iteration 100), and no iteration may overflow."""
+    wl = replace(I.C3, steps=120)
+    step = St.TransformerStep(wl, prechecked=True, flat_update=True)
+    step.set_batch(wl.batch())
+    step.step()
+    graph = _graph_step(step)
+    for _ in range(wl.steps - 1):
+        graph.replay()
+    s = step.state()
+    ost = O.ScaleState(scale=float(wl.scale.init_scale), growth_interval=wl.scale.growth_interval)
+    for i in range(wl.steps):
+        O.loss_scale_update(ost, int(s.hist_found_inf[i]))
+    assert [s.hist_scale[i] for i in range(wl.steps)] == [h[0] for h in ost.history]
+    assert [s.hist_scale[i] for i in range(wl.steps)] == [2.0 ** 15] * 100 + [2.0 ** 16] * 20
+    assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (ost.scale, ost.good_steps, 120, 0)
+    assert np.isfinite(float(step.loss))
+
+
+def test_config4_full_size():
+    """Vocabulary projection + cross-entropy at 8192 x 32768: steps 0-4 free-running against the oracle (overflow
+    forced at step 3 by the x1e4 hidden row, scale halved for step 4), then the rest on the GPU alone with the flag
+    stream replayed through the oracle's state machine (golden sequence c4)."""
+    from test_oracle_optimizer import _golden
+    wl = I.C4
+    bf = _xent_batches(wl)
+    step = St.XentStep(wl)
+    tr = Mo.Trainer(MIXED, wl.masters(), wl.opt, wl.scale)
+    for k in range(5):
+        b = bf(k)
+        step.set_batch(b)
+        keep = {}
+        ob = Mo.island_batch(MIXED, b)
+        w_before = {n: np32(step.P.w16[n]) for n in step.P.names}
+        step.forward_backward()
+        loss_ref, g_ref = Mo.xent_head_fwd_bwd(MIXED, w_before, ob, float(step.state().scale), keep=keep)
+        bad = O.has_nonfinite(MIXED, list(g_ref.values()))
+        assert bad == (k == wl.blowup_step)
+        assert abs(float(step.loss) - float(loss_ref)) <= 2e-4 * abs(float(loss_ref))
+        if not bad:
+            for n in step.P.names:
+                assert rel_fro(np32(step.P.g16[n]), g_ref[n]) <= GRAD_TOL, (k, n)
+            assert rel_fro(np32(step.dh), keep["dh"]) <= GRAD_TOL
+        else:
+            assert O.has_nonfinite(MIXED, [np32(step.P.g16["w"])])
+        step.optimizer()
+        print(f"config 4 step {k}: loss {float(step.loss):.4f} overflow={bad}", flush=True)
+    for k in range(5, wl.steps):
+        step.set_batch(bf(k)) if k == 5 else None
+        step.step()
+    s, g = step.state(), _golden()["c4"]
+    assert [s.hist_scale[i] for i in range(wl.steps)] == g["seq"]
+    assert [s.hist_found_inf[i] for i in range(wl.steps)] == [int(i in g["ovf"]) for i in range(wl.steps)]
+    assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (g["final"], g["good"], g["t"], g["skipped"])
+
+
+def test_config5_full_size():
+    """GNMT-like LSTM stack at full size: one teacher-forced iteration against the oracle, then 20 iterations on the
+    GPU with the scale sequence checked against the hand-derived one (c5)."""
+    from test_oracle_optimizer import _golden
+    wl = I.C5
+    f = Mo.make_lstm_fwd_bwd(wl.n_layers)
+    batch = wl.batch()
+    step = St.LSTMStep(wl)
+    step.set_batch(batch)
+    # 4 layers x 50 time steps of recurrence compound fp16 roundings to ~1e-3 at the bottom layer, for the
+    # oracle as much as for the GPU: the whole-network check is "as close to fp64 as the oracle" (the
+    # reduced-size run above holds 1e-3 directly, and the cell / gate kernels are checked in isolation).
+    teacher_forced(step, wl, f, batch, 1, grad_mode="vs_fp64")
+    for _ in range(wl.steps - 1):
+        step.step()
+    s, g = step.state(), _golden()["c5"]
+    assert [s.hist_scale[i] for i in range(wl.steps)] == g["seq"]
+    assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (g["final"], g["good"], g["t"], g["skipped"])
+    assert np.isfinite(float(step.loss))
+
+
+def test_graph_replay_matches_eager_small():
+    """HIP-graph capture of a whole iteration (no memset nodes: fills are kernels) replays bit-identically, with
+    eager work and synchronisation between replays."""
+    wl, batch = I.C3_SMALL, I.C3_SMALL.batch()
+    a, b = St.TransformerStep(wl), St.TransformerStep(wl)
+    for s in (a, b):
+        s.set_batch(batch)
+        s.step()
+    graph = _graph_step(a)
+    for _ in range(4):
+        graph.replay()
+        b.step()
+        torch.cuda.synchronize()
+        assert float(a.loss) == float(b.loss) and torch.equal(a.P.w32_arena, b.P.w32_arena)
+    assert a.state().opt_step == b.state().opt_step == 5
