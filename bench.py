@@ -150,6 +150,13 @@ def main():
     t_upd = _time_calls(torch, lambda: B.mp_unscale_check_update(step.P.flat_list, 1, step.cfg, step.st, 1), 10)
     t_upd_chk = _time_calls(torch, lambda: B.mp_unscale_check_update(step.P.flat_list, 1, step.cfg, step.st, 0), 10)
 
+    # one plain device copy of known size (256 MiB read + 256 MiB write): the calibration launch for the
+    # FETCH_SIZE / WRITE_SIZE counters when this script runs under rocprofv3 --pmc
+    cal_src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+
     out = {
         "metric": "training tokens/sec (fp16 MP step, Transformer-big layer); MFMA util %",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

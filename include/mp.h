@@ -161,6 +161,13 @@ int mp_gemm_bwd_dw(const mp_gemm_desc* desc /* host */, const mp_half* dY, const
                    mp_half* dW, mp_half* db, mp_scale_state* st, void* ws, size_t ws_bytes,
                    mp_stream stream);
 
+/* Tuning aid, process-wide and not thread-safe: force every following contraction onto tile shape `tile`
+ * (index into the library's tile table: 0 = 256x256, 1 = 256x128, 2 = 128x256, 3 = 128x128, 4 = 128x64,
+ * 5 = 64x128, 6 = 64x64, 7 = 32x128) and, where splitting the contraction is allowed, onto `splits` splits.
+ * tile < 0 restores the built-in choice.  Results do not depend on it beyond fp32 summation order.
+ * Note that mp_gemm_bwd_dw_workspace_bytes answers for the choice in force when it is called. */
+int mp_gemm_tuning_override(int tile, int splits);
+
 /* db[cols] = RNE16( column sums (fp32) of dY[rows, cols] ); optional overflow flag as above.
  * Workspace: mp_colsum_workspace_bytes(rows, cols). */
 size_t mp_colsum_workspace_bytes(int rows, int cols);

@@ -90,6 +90,10 @@ def mp_gemm_bwd_dw(desc: GemmDesc, dY, X, dW, db=None, st=None, ws=None):
                                    0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 
+def mp_gemm_tuning_override(tile: int, splits: int = 1):
+    _check(L.load().mp_gemm_tuning_override(tile, splits))
+
+
 def mp_colsum_workspace_bytes(rows: int, cols: int) -> int:
     return L.load().mp_colsum_workspace_bytes(rows, cols)
 

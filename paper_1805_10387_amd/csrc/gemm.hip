@@ -580,16 +580,14 @@ static int launch_tile(int t, const GemmArgs& g, dim3 grid, hipStream_t hs) {
 struct Plan {
     int tile, splits, k_per_split;
 };
+static int g_force_tile = -1, g_force_splits = 1;
 
 // Pick the tile shape (and split count when allowed) that minimises an estimate of run time:
 // rounds of 256 workgroups x work per workgroup / shape efficiency.
 static Plan make_plan(int M, int N, int K, long long batches, bool allow_split) {
-    // tuning aid: MP_GEMM_TILE=<index into kTiles> forces a tile shape, MP_GEMM_SPLITS=<n> a split count
-    static const char* force_tile  = getenv("MP_GEMM_TILE");
-    static const char* force_split = getenv("MP_GEMM_SPLITS");
-    if (force_tile) {
-        int t = atoi(force_tile), sp = (force_split && allow_split) ? atoi(force_split) : 1;
-        if (t < 0 || t >= kNumTiles) t = 0;
+    // tuning aid (mp_gemm_tuning_override): force a tile shape / split count
+    if (g_force_tile >= 0) {
+        int t = g_force_tile < kNumTiles ? g_force_tile : 0, sp = allow_split ? g_force_splits : 1;
         if (sp < 1) sp = 1;
         const int kps = ((K + sp - 1) / sp + BK - 1) / BK * BK;
         return Plan{t, sp, kps > 0 ? kps : BK};
@@ -704,6 +702,13 @@ static size_t splitk_floats(int M, int N, int K) {
     if (M <= 0 || N <= 0 || (N & 3) != 0) return 0;
     const Plan p = make_plan(M, N, K, 1, true);
     return p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N : 0;
+}
+
+extern "C" int mp_gemm_tuning_override(int tile, int splits) {
+    MP_REQUIRE(tile < kNumTiles, "mp_gemm_tuning_override: tile index %d out of range (%d shapes)", tile, kNumTiles);
+    g_force_tile   = tile;
+    g_force_splits = splits > 0 ? splits : 1;
+    return MP_OK;
 }
 
 extern "C" size_t mp_gemm_bwd_dw_workspace_bytes(const mp_gemm_desc* d, int with_db) {
