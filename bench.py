@@ -45,6 +45,8 @@ def gemm_roofline(torch, B, step, reps=20):
     """Time each distinct dense contraction of one layer in isolation (same descriptors, same buffers as
     the step uses) and aggregate: algorithmic flops = 2 M N K per launch."""
     wl, w, g, a = step.wl, step.P.w16, step.P.g16, step.act[0]
+    tb = step.tmp[0]
+    dqkv, dz1, dz2, df = tb["dqkv"], tb["dz1"], tb["dz2"], tb["df"]
     T, d, f = wl.tokens, wl.d_model, wl.d_ff
     x, ws, st = step.x0, step.ws, step.st
     calls = {
@@ -52,14 +54,14 @@ def gemm_roofline(torch, B, step, reps=20):
         "fwd_o": (2.0 * T * d * d, lambda: B.mp_gemm_fwd(step.d_o, a["ctx"], w["l0.wo"], w["l0.bo"], None, a["a"])),
         "fwd_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_fwd(step.d_f1, a["y1"], w["l0.w1"], w["l0.b1"], None, a["f"])),
         "fwd_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_fwd(step.d_f2, a["f"], w["l0.w2"], w["l0.b2"], None, a["g"])),
-        "dx_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dx(step.d_qkv, step.dqkv, w["l0.wqkv"], step.gbuf[1], add=step.dz1, ld_aux=d)),
-        "dx_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dx(step.d_o, step.dz1, w["l0.wo"], step.dctx)),
-        "dx_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f1, step.df, w["l0.w1"], step.dy1, add=step.dz2, ld_aux=d)),
-        "dx_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f2, step.dz2, w["l0.w2"], step.df, relu_src=a["f"], ld_aux=f)),
-        "dw_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dw(step.d_qkv, step.dqkv, x, g["l0.wqkv"], None, st, ws)),
-        "dw_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dw(step.d_o, step.dz1, a["ctx"], g["l0.wo"], None, st, ws)),
-        "dw_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f1, step.df, a["y1"], g["l0.w1"], None, st, ws)),
-        "dw_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f2, step.dz2, a["f"], g["l0.w2"], None, st, ws)),
+        "dx_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dx(step.d_qkv, dqkv, w["l0.wqkv"], step.gbuf[1], add=dz1, ld_aux=d)),
+        "dx_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dx(step.d_o, dz1, w["l0.wo"], step.dctx)),
+        "dx_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f1, df, w["l0.w1"], step.dy1, add=dz2, ld_aux=d)),
+        "dx_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f2, dz2, w["l0.w2"], df, relu_src=a["f"], ld_aux=f)),
+        "dw_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dw(step.d_qkv, dqkv, x, g["l0.wqkv"], None, st, ws)),
+        "dw_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dw(step.d_o, dz1, a["ctx"], g["l0.wo"], None, st, ws)),
+        "dw_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f1, df, a["y1"], g["l0.w1"], None, st, ws)),
+        "dw_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f2, dz2, a["f"], g["l0.w2"], None, st, ws)),
     }
     per, flops, secs = {}, 0.0, 0.0
     for name, (fl, fn) in calls.items():
@@ -101,6 +103,7 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
+    ap.add_argument("--two-streams", action="store_true", help="enqueue the weight-gradient products on a second stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     args = ap.parse_args()
@@ -117,7 +120,7 @@ def main():
 
     torch.cuda.set_device(0)
     wl = I.C3
-    step = St.TransformerStep(wl, prechecked=True, flat_update=True)
+    step = St.TransformerStep(wl, prechecked=True, flat_update=True, two_streams=args.two_streams)
     step.set_batch(wl.batch())
     for _ in range(max(args.warmup, 1)):
         step.step()
@@ -166,7 +169,8 @@ def main():
                                "64 sequences x 128 tokens = 8192 tokens, fp16 with fp32 masters, MSE, Adam, "
                                "dynamic loss scale 2^15 / growth 100",
                    "launch": "HIP graph replay" if not args.no_graph else "eager ctypes launches",
-                   "overflow_check": "in gradient-producing epilogues (MP_UPDATE_PRECHECKED)", "update_list": "one flat descriptor"},
+                   "overflow_check": "in gradient-producing epilogues (MP_UPDATE_PRECHECKED)", "update_list": "one flat descriptor",
+                   "streams": "weight-gradient products on a second stream" if args.two_streams else "one stream"},
         "step_gemm_tflops": wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12,
         "step_mfma_util_pct": 100.0 * wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12 / PEAK_FP16_TFLOPS,
         "final_loss": loss, "loss_scale": st.scale, "opt_steps": st.opt_step, "skipped": st.skipped_steps,

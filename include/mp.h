@@ -206,12 +206,14 @@ int mp_layernorm_fwd(int rows, int d, const mp_half* x, const mp_half* a, const 
 
 /* dz = RNE16( rstd (g - mean_d(g) - xhat mean_d(g xhat)) ), g = dy gamma, xhat = (x + a - mean) rstd;
  * dgamma[d] = RNE16( sum_rows dy xhat ), dbeta[d] = RNE16( sum_rows dy ).  dz is the gradient of both
- * x and a.  Optional overflow flag on dgamma/dbeta.  Workspace: mp_layernorm_bwd_workspace_bytes. */
+ * x and a.  If dz_colsum != NULL it also receives RNE16( column sums over rows of the stored dz ): the bias
+ * gradient of the linear layer whose output entered this LayerNorm, at no extra pass over memory.
+ * Optional overflow flag on dgamma / dbeta / dz_colsum.  Workspace: mp_layernorm_bwd_workspace_bytes. */
 size_t mp_layernorm_bwd_workspace_bytes(int rows, int d);
 int mp_layernorm_bwd(int rows, int d, const mp_half* dy, const mp_half* x, const mp_half* a,
                      const mp_half* gamma, const float* mean, const float* rstd, mp_half* dz,
-                     mp_half* dgamma, mp_half* dbeta, mp_scale_state* st, void* ws, size_t ws_bytes,
-                     mp_stream stream);
+                     mp_half* dgamma, mp_half* dbeta, mp_half* dz_colsum, mp_scale_state* st, void* ws,
+                     size_t ws_bytes, mp_stream stream);
 
 /* Row softmax of attention scores: p = RNE16( softmax_fp32(s) ), rows x cols, contiguous rows of
  * length cols with leading dimension ld (p may alias s). */

@@ -5,7 +5,8 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libmp.so")
+# MP_LIBMP_PATH lets a developer load another build of the same library (e.g. an experiment)
+LIB_PATH = os.environ.get("MP_LIBMP_PATH") or os.path.join(HERE, "libmp.so")
 
 MP_HISTORY = 4096
 MP_OK, MP_E_INVAL, MP_E_UNSUPPORTED, MP_E_WORKSPACE, MP_E_HIP = 0, -1, -2, -3, -4
@@ -62,7 +63,7 @@ SIGNATURES = {
     "mp_softmax_xent_scaled": (_I, [_I, _I, _P, _I, _P, _P, _P, _P, _P, _SZ, _P]),
     "mp_layernorm_fwd": (_I, [_I, _I, _P, _P, _P, _P, _F, _P, _P, _P, _P]),
     "mp_layernorm_bwd_workspace_bytes": (_SZ, [_I, _I]),
-    "mp_layernorm_bwd": (_I, [_I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mp_layernorm_bwd": (_I, [_I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "mp_softmax_fwd": (_I, [_I64, _I, _P, _P, _I, _P]),
     "mp_softmax_bwd": (_I, [_I64, _I, _P, _P, _P, _I, _P]),
     "mp_lstm_cell_fwd": (_I, [_I, _I, _P, _I, _P, _P, _P, _I, _P, _I, _P]),

@@ -127,9 +127,9 @@ def mp_layernorm_bwd_workspace_bytes(rows: int, d: int) -> int:
     return L.load().mp_layernorm_bwd_workspace_bytes(rows, d)
 
 
-def mp_layernorm_bwd(rows, d, dy, x, a, gamma, mean, rstd, dz, dgamma, dbeta, st, ws):
+def mp_layernorm_bwd(rows, d, dy, x, a, gamma, mean, rstd, dz, dgamma, dbeta, st, ws, dz_colsum=None):
     _check(L.load().mp_layernorm_bwd(rows, d, _p(dy), _p(x), _p(a), _p(gamma), _p(mean), _p(rstd), _p(dz), _p(dgamma),
-                                     _p(dbeta), _p(st), _p(ws), ws.numel() * ws.element_size(), _stream()))
+                                     _p(dbeta), _p(dz_colsum), _p(st), _p(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def mp_softmax_fwd(rows, cols, s, p, ld):

@@ -29,25 +29,41 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
 // out16[c] = RNE16( sum_p part[p * stride + c] ) in a fixed order; optional non-finite flag.
 // Workgroup = 32 columns x 8 part-lanes: lane q sums parts q, q+8, ... ; the 8 lane sums are then
 // added in lane order.
+struct FinishOuts {
+    uint16_t* p[3];  // output of segment s covers partial columns [s*n, (s+1)*n)
+};
 __global__ __launch_bounds__(GL_THREADS) void finish_colsum_kernel(const float* __restrict__ part, int nparts,
-                                                                   long long stride, int n, uint16_t* __restrict__ out16,
+                                                                   long long stride, int n, int nseg, FinishOuts outs,
                                                                    mp_scale_state* st) {
     __shared__ float sm[8][33];
     const int cl = threadIdx.x & 31, q = threadIdx.x >> 5;
     const int c  = blockIdx.x * 32 + cl;
+    const int nt = n * nseg;
     float     acc = 0.f;
-    if (c < n)
-        for (int p = q; p < nparts; p += 8) acc += part[(long long)p * stride + c];
+    if (c < nt) {
+        // eight loads in flight per lane; the order of additions is fixed (p ascending)
+        int p = q;
+        for (; p + 56 < nparts; p += 64) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = part[(long long)(p + 8 * u) * stride + c];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += t[u];
+        }
+        for (; p < nparts; p += 8) acc += part[(long long)p * stride + c];
+    }
     sm[q][cl] = acc;
     __syncthreads();
     bool bad = false;
-    if (q == 0 && c < n) {
+    if (q == 0 && c < nt) {
         float t = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) t += sm[j][cl];
-        const uint16_t h = f2h(t);
-        out16[c]         = h;
-        bad              = half_nonfinite(h);
+        const uint16_t h   = f2h(t);
+        const int      seg = c / n;
+        uint16_t*      o   = seg == 0 ? outs.p[0] : (seg == 1 ? outs.p[1] : outs.p[2]);
+        o[c - seg * n]     = h;
+        bad                = half_nonfinite(h);
     }
     if (st != nullptr && __any(bad)) {
         if ((threadIdx.x & 63) == 0) atomicOr(&st->found_inf, 1);
@@ -159,7 +175,9 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_fwd_kernel(int rows, int
 
 // Backward: each wave walks rows  row = wave_global, wave_global + n_waves, ...  and keeps the
 // column sums of dy*xhat and dy for its rows in registers; they are combined per workgroup in LDS
-// and written as partials part[block][2][d].
+// and written as partials part[block][NS][d] (NS = 3 with ZSUM: also the column sums of the stored dz,
+// which is the bias gradient of the linear layer whose output fed this LayerNorm).
+template <bool ZSUM>
 __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int d, const uint16_t* __restrict__ dy,
                                                                    const uint16_t* __restrict__ x,
                                                                    const uint16_t* __restrict__ a,
@@ -167,15 +185,20 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int
                                                                    const float* __restrict__ mean_i,
                                                                    const float* __restrict__ rstd_i,
                                                                    uint16_t* __restrict__ dz, float* __restrict__ part) {
-    extern __shared__ float sm[];  // [GL_WAVES][2][d]
+    extern __shared__ float sm[];  // [GL_WAVES][NS][d]
+    constexpr int NS = ZSUM ? 3 : 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nvec = d >> 3;
-    float     gam[LN_MAXV][8], sg[LN_MAXV][8], sb[LN_MAXV][8];
+    float     gam[LN_MAXV][8], sg[LN_MAXV][8], sb[LN_MAXV][8], sz[ZSUM ? LN_MAXV : 1][8];
 #pragma unroll
     for (int i = 0; i < LN_MAXV; ++i) {
         const int v = i * 64 + lane;
 #pragma unroll
         for (int k = 0; k < 8; ++k) sg[i][k] = sb[i][k] = gam[i][k] = 0.f;
+        if (ZSUM) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) sz[i][k] = 0.f;
+        }
         if (v < nvec) unpack8(*reinterpret_cast<const uint4*>(gamma + v * 8), gam[i]);
     }
     for (int row = blockIdx.x * GL_WAVES + wave; row < rows; row += gridDim.x * GL_WAVES) {
@@ -217,6 +240,10 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int
 #pragma unroll
                 for (int k = 0; k < 8; ++k) o[k] = rstd * (g[i][k] - m1 - xh[i][k] * m2);
                 *reinterpret_cast<uint4*>(dz + base + v * 8) = pack8(o);
+                if (ZSUM) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) sz[i][k] += round16(o[k]);  // sums the stored (fp16) values
+                }
             }
         }
     }
@@ -226,18 +253,19 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int
         if (v < nvec) {
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-                sm[(wave * 2 + 0) * d + v * 8 + k] = sg[i][k];
-                sm[(wave * 2 + 1) * d + v * 8 + k] = sb[i][k];
+                sm[(wave * NS + 0) * d + v * 8 + k] = sg[i][k];
+                sm[(wave * NS + 1) * d + v * 8 + k] = sb[i][k];
+                if (ZSUM) sm[(wave * NS + 2) * d + v * 8 + k] = sz[i][k];
             }
         }
     }
     __syncthreads();
-    for (int c = threadIdx.x; c < 2 * d; c += GL_THREADS) {
+    for (int c = threadIdx.x; c < NS * d; c += GL_THREADS) {
         const int which = c / d, col = c - which * d;
         float     t     = 0.f;
 #pragma unroll
-        for (int w = 0; w < GL_WAVES; ++w) t += sm[(w * 2 + which) * d + col];
-        part[(long long)blockIdx.x * 2 * d + c] = t;
+        for (int w = 0; w < GL_WAVES; ++w) t += sm[(w * NS + which) * d + col];
+        part[(long long)blockIdx.x * NS * d + c] = t;
     }
 }
 
@@ -478,8 +506,9 @@ extern "C" int mp_colsum(int rows, int cols, const mp_half* dY, int ld, mp_half*
     else
         hipLaunchKernelGGL(colsum_kernel<1>, grid, dim3(GL_THREADS), 0, hs, rows, cols, ld, dY, rpb, part);
     MP_LAUNCH_CHECK("mp_colsum");
+    FinishOuts outs{{db, nullptr, nullptr}};
     hipLaunchKernelGGL(finish_colsum_kernel, dim3((cols + 31) / 32), dim3(GL_THREADS), 0, hs, part, rb,
-                       (long long)cols, cols, db, st);
+                       (long long)cols, cols, 1, outs, st);
     MP_LAUNCH_CHECK("mp_colsum(finish)");
     return MP_OK;
 }
@@ -504,7 +533,7 @@ extern "C" int mp_layernorm_fwd(int rows, int d, const mp_half* x, const mp_half
 }
 
 static int ln_bwd_blocks(int rows) {
-    int nb = (rows + GL_WAVES * 8 - 1) / (GL_WAVES * 8);  // about 8 rows per wave
+    int nb = (rows + GL_WAVES * 4 - 1) / (GL_WAVES * 4);  // about 4 rows per wave
     if (nb > 512) nb = 512;
     if (nb < 1) nb = 1;
     return nb;
@@ -512,12 +541,13 @@ static int ln_bwd_blocks(int rows) {
 
 extern "C" size_t mp_layernorm_bwd_workspace_bytes(int rows, int d) {
     if (rows <= 0 || d <= 0) return 0;
-    return (size_t)ln_bwd_blocks(rows) * 2 * d * sizeof(float);
+    return (size_t)ln_bwd_blocks(rows) * 3 * d * sizeof(float);
 }
 
 extern "C" int mp_layernorm_bwd(int rows, int d, const mp_half* dy, const mp_half* x, const mp_half* a,
                                 const mp_half* gamma, const float* mean, const float* rstd, mp_half* dz, mp_half* dgamma,
-                                mp_half* dbeta, mp_scale_state* st, void* ws, size_t ws_bytes, mp_stream stream) {
+                                mp_half* dbeta, mp_half* dz_colsum, mp_scale_state* st, void* ws, size_t ws_bytes,
+                                mp_stream stream) {
     MP_REQUIRE(rows > 0 && d > 0, "mp_layernorm_bwd: bad shape rows=%d d=%d", rows, d);
     MP_REQUIRE(dy && x && gamma && mean && rstd && dz && dgamma && dbeta, "mp_layernorm_bwd: NULL argument");
     if (!ln_shape_ok(d)) {
@@ -532,16 +562,21 @@ extern "C" int mp_layernorm_bwd(int rows, int d, const mp_half* dy, const mp_hal
         return MP_E_WORKSPACE;
     }
     const int   nb   = ln_bwd_blocks(rows);
+    const int   ns   = dz_colsum ? 3 : 2;
     float*      part = static_cast<float*>(ws);
     hipStream_t hs   = as_stream(stream);
-    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(nb), dim3(GL_THREADS), (size_t)GL_WAVES * 2 * d * sizeof(float), hs, rows, d,
-                       dy, x, a, gamma, mean, rstd, dz, part);
+    const size_t lds = (size_t)GL_WAVES * ns * d * sizeof(float);
+    if (dz_colsum)
+        hipLaunchKernelGGL(layernorm_bwd_kernel<true>, dim3(nb), dim3(GL_THREADS), lds, hs, rows, d, dy, x, a, gamma, mean,
+                           rstd, dz, part);
+    else
+        hipLaunchKernelGGL(layernorm_bwd_kernel<false>, dim3(nb), dim3(GL_THREADS), lds, hs, rows, d, dy, x, a, gamma, mean,
+                           rstd, dz, part);
     MP_LAUNCH_CHECK("mp_layernorm_bwd");
-    const int fb = (d + 31) / 32;
-    hipLaunchKernelGGL(finish_colsum_kernel, dim3(fb), dim3(GL_THREADS), 0, hs, part, nb, (long long)2 * d, d, dgamma, st);
-    MP_LAUNCH_CHECK("mp_layernorm_bwd(dgamma)");
-    hipLaunchKernelGGL(finish_colsum_kernel, dim3(fb), dim3(GL_THREADS), 0, hs, part + d, nb, (long long)2 * d, d, dbeta, st);
-    MP_LAUNCH_CHECK("mp_layernorm_bwd(dbeta)");
+    FinishOuts outs{{dgamma, dbeta, dz_colsum}};
+    hipLaunchKernelGGL(finish_colsum_kernel, dim3((ns * d + 31) / 32), dim3(GL_THREADS), 0, hs, part, nb, (long long)ns * d,
+                       d, ns, outs, st);
+    MP_LAUNCH_CHECK("mp_layernorm_bwd(finish)");
     return MP_OK;
 }
 

@@ -153,11 +153,13 @@ class MLPStep(_StepBase):
 class TransformerStep(_StepBase):
     """Stack of post-LayerNorm encoder layers with an MSE loss on the last output (configs 2, 3)."""
 
-    def __init__(self, wl, masters=None, **kw):
+    def __init__(self, wl, masters=None, two_streams=False, **kw):
         if masters is None:
             masters = {f"l{i}.{k}": v for i, lay in enumerate(wl.masters()) for k, v in lay.items()}
         super().__init__(masters, wl.opt, wl.scale, **kw)
         self.wl = wl
+        self.two_streams = two_streams
+        self.side_stream = torch.cuda.Stream() if two_streams else None
         T, d, f, h, S, NB = wl.tokens, wl.d_model, wl.d_ff, wl.n_heads, wl.seq_len, wl.n_seq
         dk = d // h
         e16 = lambda *s: torch.empty(s, dtype=torch.float16, device="cuda")
@@ -170,8 +172,8 @@ class TransformerStep(_StepBase):
                                  rstd2=e32(T)))
         # backward temporaries, shared by all layers
         self.gbuf = [e16(T, d), e16(T, d)]
-        self.dz2, self.df, self.dy1, self.dz1 = e16(T, d), e16(T, f), e16(T, d), e16(T, d)
-        self.dctx, self.dp, self.dqkv = e16(T, d), e16(NB, h, S, S), e16(T, 3 * d)
+        self.tmp = [dict(dz2=e16(T, d), df=e16(T, f), dz1=e16(T, d), dqkv=e16(T, 3 * d)) for _ in range(2)]
+        self.dy1, self.dctx, self.dp = e16(T, d), e16(T, d), e16(NB, h, S, S)
         G = B.gemm_desc
         self.d_qkv = G(T, 3 * d, d, epilogue=ML.MP_EPI_BIAS)
         self.d_o = G(T, d, d, epilogue=ML.MP_EPI_BIAS)
@@ -187,6 +189,7 @@ class TransformerStep(_StepBase):
         need += [B.mp_gemm_bwd_dw_workspace_bytes(self.d_s, False), B.mp_gemm_bwd_dw_workspace_bytes(self.d_c, False),
                  B.mp_layernorm_bwd_workspace_bytes(T, d), B.mp_loss_workspace_bytes(T, d)]
         self._alloc_ws(max(need))
+        self.ws_side = torch.empty_like(self.ws)
 
     def set_batch(self, batch):
         self.x0.copy_(_h16(batch["x"]))
@@ -212,41 +215,71 @@ class TransformerStep(_StepBase):
         return x
 
     def backward(self):
+        """Backward pass.  The weight-gradient products do not feed anything else in the backward pass, so
+        they are enqueued on a second stream (forked and joined with events, which HIP-graph capture records
+        as parallel branches): their prologues, epilogues and partial last rounds overlap the input-gradient
+        chain on the main stream.  Temporaries read by the side stream are double-buffered by layer parity, and
+        the main stream waits for the side work of two layers back before reusing them."""
         wl, w, g, st, ws = self.wl, self.P.w16, self.P.g16, self.st_grad, self.ws
         T, d, f, h, S, NB = wl.tokens, wl.d_model, wl.d_ff, wl.n_heads, wl.seq_len, wl.n_seq
+        main = torch.cuda.current_stream()
+        side = self.side_stream if self.two_streams else None
+        done = {}
+
+        def fork(fn):
+            """Run fn (weight-gradient calls) on the side stream after everything enqueued so far on main."""
+            if side is None:
+                fn(ws)
+                return
+            ev = torch.cuda.Event()
+            ev.record(main)
+            side.wait_event(ev)
+            with torch.cuda.stream(side):
+                fn(self.ws_side)
+
         # the layer-output gradient ping-pongs between two [T, d] buffers; the loss wrote gbuf[0]
         for i, l in enumerate(range(wl.n_layers - 1, -1, -1)):
             dy2, dx = self.gbuf[i % 2], self.gbuf[(i + 1) % 2]
             a, p = self.act[l], f"l{l}."
+            tb = self.tmp[i % 2]
+            dz2, df, dz1, dqkv = tb["dz2"], tb["df"], tb["dz1"], tb["dqkv"]
+            if side is not None and i >= 2:
+                main.wait_event(done[i - 2])        # side stream finished reading this parity's temporaries
             x = self.x0 if l == 0 else self.act[l - 1]["y2"]
-            B.mp_layernorm_bwd(T, d, dy2, a["y1"], a["g"], w[p + "ln2_g"], a["mean2"], a["rstd2"], self.dz2,
-                               g[p + "ln2_g"], g[p + "ln2_b"], st, ws)
+            # dz2 is the gradient of g = W2 f + b2 too, so its column sums are b2's gradient
+            B.mp_layernorm_bwd(T, d, dy2, a["y1"], a["g"], w[p + "ln2_g"], a["mean2"], a["rstd2"], dz2,
+                               g[p + "ln2_g"], g[p + "ln2_b"], st, ws, dz_colsum=g[p + "b2"])
             self._t("dy2", l, dy2)
-            self._t("dz2", l, self.dz2)
-            B.mp_gemm_bwd_dw(self.d_f2, self.dz2, a["f"], g[p + "w2"], g[p + "b2"], st, ws)
-            B.mp_gemm_bwd_dx(self.d_f2, self.dz2, w[p + "w2"], self.df, relu_src=a["f"], ld_aux=f)
-            self._t("df", l, self.df)
-            B.mp_gemm_bwd_dw(self.d_f1, self.df, a["y1"], g[p + "w1"], g[p + "b1"], st, ws)
-            B.mp_gemm_bwd_dx(self.d_f1, self.df, w[p + "w1"], self.dy1, add=self.dz2, ld_aux=d)
+            self._t("dz2", l, dz2)
+            fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f2, dz2, a["f"], g[p + "w2"], None, st, wsx))
+            B.mp_gemm_bwd_dx(self.d_f2, dz2, w[p + "w2"], df, relu_src=a["f"], ld_aux=f)
+            self._t("df", l, df)
+            fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f1, df, a["y1"], g[p + "w1"], g[p + "b1"], st, wsx))
+            B.mp_gemm_bwd_dx(self.d_f1, df, w[p + "w1"], self.dy1, add=dz2, ld_aux=d)
             self._t("dy1", l, self.dy1)
-            B.mp_layernorm_bwd(T, d, self.dy1, x, a["a"], w[p + "ln1_g"], a["mean1"], a["rstd1"], self.dz1,
-                               g[p + "ln1_g"], g[p + "ln1_b"], st, ws)
-            self._t("dz1", l, self.dz1)
-            B.mp_gemm_bwd_dw(self.d_o, self.dz1, a["ctx"], g[p + "wo"], g[p + "bo"], st, ws)
-            B.mp_gemm_bwd_dx(self.d_o, self.dz1, w[p + "wo"], self.dctx)
+            B.mp_layernorm_bwd(T, d, self.dy1, x, a["a"], w[p + "ln1_g"], a["mean1"], a["rstd1"], dz1,
+                               g[p + "ln1_g"], g[p + "ln1_b"], st, ws, dz_colsum=g[p + "bo"])
+            self._t("dz1", l, dz1)
+            fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_o, dz1, a["ctx"], g[p + "wo"], None, st, wsx))
+            B.mp_gemm_bwd_dx(self.d_o, dz1, w[p + "wo"], self.dctx)
             self._t("dctx", l, self.dctx)
             # attention: dP = dctx V^T, dV = P^T dctx, dS = softmax', dQ = alpha dS K, dK = alpha dS^T Q
             B.mp_gemm_bwd_dx(self.d_c, self.dctx, a["qkv"][:, 2 * d:], self.dp)
             self._t("dp", l, self.dp)
-            B.mp_gemm_bwd_dw(self.d_c, self.dctx, a["p"], self.dqkv[:, 2 * d:], None, None, ws)
+            B.mp_gemm_bwd_dw(self.d_c, self.dctx, a["p"], dqkv[:, 2 * d:], None, None, ws)
             B.mp_softmax_bwd(NB * h * S, S, a["p"], self.dp, self.dp, S)
             self._t("ds", l, self.dp)
-            B.mp_gemm_bwd_dx(self.d_s, self.dp, a["qkv"][:, d:], self.dqkv)
-            B.mp_gemm_bwd_dw(self.d_s, self.dp, a["qkv"], self.dqkv[:, d:], None, None, ws)
-            B.mp_gemm_bwd_dw(self.d_qkv, self.dqkv, x, g[p + "wqkv"], g[p + "bqkv"], st, ws)
-            self._t("dqkv", l, self.dqkv)
-            B.mp_gemm_bwd_dx(self.d_qkv, self.dqkv, w[p + "wqkv"], dx, add=self.dz1, ld_aux=d)
+            B.mp_gemm_bwd_dx(self.d_s, self.dp, a["qkv"][:, d:], dqkv)
+            B.mp_gemm_bwd_dw(self.d_s, self.dp, a["qkv"], dqkv[:, d:], None, None, ws)
+            self._t("dqkv", l, dqkv)
+            fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_qkv, dqkv, x, g[p + "wqkv"], g[p + "bqkv"], st, wsx))
+            B.mp_gemm_bwd_dx(self.d_qkv, dqkv, w[p + "wqkv"], dx, add=dz1, ld_aux=d)
             self._t("dx", l, dx)
+            if side is not None:
+                done[i] = torch.cuda.Event()
+                done[i].record(side)
+        if side is not None:
+            main.wait_stream(side)                   # every weight gradient is complete before the update
         self.dx_input = self.gbuf[wl.n_layers % 2]
 
     def forward_backward(self):

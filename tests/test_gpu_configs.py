@@ -283,6 +283,17 @@ def test_config3_reduced_prechecked_flat_update_matches_default():
     assert float(a.loss) == float(b.loss)
 
 
+def test_second_stream_for_weight_gradients_gives_the_same_bits():
+    wl, batch = I.C3_SMALL, I.C3_SMALL.batch()
+    a, b = St.TransformerStep(wl), St.TransformerStep(wl, two_streams=True)
+    for s in (a, b):
+        s.set_batch(batch)
+        for _ in range(3):
+            s.step()
+    torch.cuda.synchronize()
+    assert torch.equal(a.P.w32_arena, b.P.w32_arena) and torch.equal(a.P.g16_arena, b.P.g16_arena)
+
+
 def test_config2_full_size():
     wl = replace(I.C2, steps=12)
     _transformer(wl, 2, 12)                      # growth at step 10 is inside the free run

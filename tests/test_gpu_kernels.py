@@ -250,11 +250,17 @@ def test_layernorm_fwd_bwd(rows, d):
     mp.mp_layernorm_fwd(rows, d, xd, ad, gd, bd, L.LN_EPS, y, mean, rstd)
     assert_close16(y, y_ref, 1e-3, max_ulp=1, what="ln y")
     assert np.allclose(np32(rstd), cache[1][:, 0], rtol=1e-5)
-    dz, dg, db = empty16(rows, d), empty16(d), empty16(d)
+    dz, dg, db, dzs = empty16(rows, d), empty16(d), empty16(d), empty16(d)
     st = make_state()
     mp.mp_layernorm_bwd(rows, d, h16(dy), xd, ad, gd, mean, rstd, dz, dg, db, st,
-                        ws_bytes(mp.mp_layernorm_bwd_workspace_bytes(rows, d)))
+                        ws_bytes(mp.mp_layernorm_bwd_workspace_bytes(rows, d)), dz_colsum=dzs)
     assert_close16(dz, dz_ref, 1e-3, what="ln dz")
+    # the fused column sums are those of the dz the kernel stored
+    assert_close16(dzs, MIXED.store(np32(dz).sum(0, dtype=np.float32)), 1e-3, max_ulp=1, what="ln dz colsum")
+    dg2, db2 = empty16(d), empty16(d)
+    mp.mp_layernorm_bwd(rows, d, h16(dy), xd, ad, gd, mean, rstd, dz, dg2, db2, None,
+                        ws_bytes(mp.mp_layernorm_bwd_workspace_bytes(rows, d)))
+    assert np.array_equal(bits(dg2), bits(dg)) and np.array_equal(bits(db2), bits(db))
     assert_close16(dg, dg_ref, 1e-3, max_ulp=1, what="ln dgamma")
     assert_close16(db, db_ref, 1e-3, max_ulp=1, what="ln dbeta")
     assert mp.scale_state_read(st).found_inf == 0
