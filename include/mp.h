@@ -222,6 +222,25 @@ int mp_softmax_fwd(int64_t rows, int cols, const mp_half* s, mp_half* p, int ld,
 int mp_softmax_bwd(int64_t rows, int cols, const mp_half* p, const mp_half* dp, mp_half* ds, int ld,
                    mp_stream stream);
 
+/* Fused scaled-dot-product self-attention on a fused projection qkv[T, >= 3 d_model] (columns [0, d_model) = q,
+ * [d_model, 2 d_model) = k, [2 d_model, 3 d_model) = v; head h owns columns [h d_head, (h+1) d_head) of each;
+ * sequence b owns rows [b seq_len, (b+1) seq_len)).  One workgroup per (sequence, head):
+ *     s = RNE16(alpha q k^T),  p = RNE16(softmax_fp32(s)),  ctx = RNE16(p v)
+ * with the same storage points as the unfused chain mp_gemm_fwd -> mp_softmax_fwd -> mp_gemm_fwd, but s never
+ * reaches memory.  p (device fp16 [n_seq, n_heads, seq_len, seq_len]) is kept for the backward pass; ctx has the
+ * heads side by side (leading dimension ld_ctx).  No mask, no dropout.
+ * Supported: d_head == 64, seq_len a multiple of 8 up to 128; otherwise MP_E_UNSUPPORTED (use the unfused chain). */
+int mp_attention_fwd(int n_seq, int n_heads, int seq_len, int d_head, const mp_half* qkv, int ld_qkv, float alpha,
+                     mp_half* p, mp_half* ctx, int ld_ctx, mp_stream stream);
+
+/* Backward of the above from the stored p:
+ *     dP = RNE16(dctx v^T),  dS = RNE16(p (dP - sum_n dP p)),
+ *     dV = RNE16(p^T dctx),  dQ = RNE16(alpha dS k),  dK = RNE16(alpha dS^T q),
+ * written into dqkv (same column layout as qkv, leading dimension ld_dqkv). */
+int mp_attention_bwd(int n_seq, int n_heads, int seq_len, int d_head, const mp_half* qkv, int ld_qkv, float alpha,
+                     const mp_half* p, const mp_half* dctx, int ld_ctx, mp_half* dqkv, int ld_dqkv,
+                     mp_stream stream);
+
 /* LSTM cell, gate blocks ordered (i, f, g, o) in gates[B, 4H] (leading dimension ldg):
  *   c = sigma(f) c_prev + sigma(i) tanh(g)   (fp32, never rounded),  h = RNE16( sigma(o) tanh(c) ).
  * c_prev, c: device fp32 [B, H] contiguous.  h is written to h_out (ld ldh) and, if h_out2 != NULL,

@@ -66,6 +66,8 @@ SIGNATURES = {
     "mp_layernorm_bwd": (_I, [_I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "mp_softmax_fwd": (_I, [_I64, _I, _P, _P, _I, _P]),
     "mp_softmax_bwd": (_I, [_I64, _I, _P, _P, _P, _I, _P]),
+    "mp_attention_fwd": (_I, [_I, _I, _I, _I, _P, _I, _F, _P, _P, _I, _P]),
+    "mp_attention_bwd": (_I, [_I, _I, _I, _I, _P, _I, _F, _P, _P, _I, _P, _I, _P]),
     "mp_lstm_cell_fwd": (_I, [_I, _I, _P, _I, _P, _P, _P, _I, _P, _I, _P]),
     "mp_lstm_cell_bwd": (_I, [_I, _I, _P, _I, _P, _P, _P, _I, _P, _I, _P, _P, _P]),
     "mp_cast_f32_to_f16": (_I, [_SZ, _P, _P, _P]),

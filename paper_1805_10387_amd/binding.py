@@ -140,6 +140,15 @@ def mp_softmax_bwd(rows, cols, p, dp, ds, ld):
     _check(L.load().mp_softmax_bwd(rows, cols, _p(p), _p(dp), _p(ds), ld, _stream()))
 
 
+def mp_attention_fwd(n_seq, n_heads, seq_len, d_head, qkv, ld_qkv, alpha, p, ctx, ld_ctx):
+    _check(L.load().mp_attention_fwd(n_seq, n_heads, seq_len, d_head, _p(qkv), ld_qkv, alpha, _p(p), _p(ctx), ld_ctx, _stream()))
+
+
+def mp_attention_bwd(n_seq, n_heads, seq_len, d_head, qkv, ld_qkv, alpha, p, dctx, ld_ctx, dqkv, ld_dqkv):
+    _check(L.load().mp_attention_bwd(n_seq, n_heads, seq_len, d_head, _p(qkv), ld_qkv, alpha, _p(p), _p(dctx), ld_ctx,
+                                     _p(dqkv), ld_dqkv, _stream()))
+
+
 def mp_lstm_cell_fwd(B, H, gates, ldg, c_prev, c, h_out, ldh, h_out2=None, ldh2=0):
     _check(L.load().mp_lstm_cell_fwd(B, H, _p(gates), ldg, _p(c_prev), _p(c), _p(h_out), ldh, _p(h_out2), ldh2, _stream()))
 

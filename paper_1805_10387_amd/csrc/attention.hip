@@ -1,0 +1,375 @@
+// Fused scaled-dot-product self-attention for short sequences (seq_len <= 128, head size 64): one
+// workgroup per (sequence, head), scores and probabilities never leave the chip except for the
+// fp16 probability matrix the backward pass re-reads.  Same arithmetic and storage points as the
+// unfused chain of products (paper Section 3.1: fp16 operands, fp32 accumulation, one RNE per stored
+// tensor; softmax is an fp32 island, Section 3.2):
+//     s  = RNE16(alpha q k^T)      p  = RNE16(softmax_fp32(s))      ctx = RNE16(p v)
+//     dP = RNE16(dctx v^T)         dS = RNE16(p (dP - sum_n dP p))
+//     dV = RNE16(p^T dctx)         dQ = RNE16(alpha dS k)           dK = RNE16(alpha dS^T q)
+// What is saved is HBM traffic: the unfused chain writes and re-reads the [seq, seq] score-sized
+// tensors nine times per layer.
+//
+// Matrix-core conventions (v_mfma_f32_32x32x16_f16, operands A then B): a lane supplies 8 k-values of row
+// lane%32 of each operand, lanes 0-31 and 32-63 (half hf) covering two disjoint k-sets; the result lane
+// holds D[i][j] for j = lane%32 and i = 8(r/4) + 4 hf + r%4, r = 0..15.  The k-order inside one
+// instruction is free as long as both operands agree, which lets the probability registers of the
+// score product feed the next product directly: for 32-key tile t and half-slice s a lane of half hf
+// uses keys 32t + 16s + 4hf + {0..3} and 32t + 16s + 8 + 4hf + {0..3}.
+#include "common.hpp"
+
+#include <mutex>
+
+namespace mp {
+
+constexpr int AT_THREADS = 256;
+constexpr int AT_S       = 128;  // maximum sequence length (keys held per workgroup)
+constexpr int AT_D       = 64;   // head size
+typedef unsigned u32x4a __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2a __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ f16x8 as_f16x8(u32x4a v) {
+    union { u32x4a u; f16x8 h; } c; c.u = v; return c.h;
+}
+__device__ __forceinline__ f16x8 join_f16x8(u32x2a lo, u32x2a hi) {
+    union { u32x4a u; f16x8 h; } c; c.u = u32x4a{lo.x, lo.y, hi.x, hi.y}; return c.h;
+}
+__device__ __forceinline__ unsigned pack2(float a, float b) { return (unsigned)f2h(a) | ((unsigned)f2h(b) << 16); }
+
+// 16 bytes = 8 consecutive head-dimension values of row `row` (rows >= rows_valid read as zero)
+__device__ __forceinline__ u32x4a load_row8(const uint16_t* base, int ld, int row, int rows_valid, int col) {
+    if (row < rows_valid) return *reinterpret_cast<const u32x4a*>(base + (long long)row * ld + col);
+    return u32x4a{0u, 0u, 0u, 0u};
+}
+
+// LDS matrix T[R rows][128 halves] (256-byte rows, 16 slots of 16 bytes), slot index XOR (row & 15) so that 16
+// consecutive rows read the same logical slot from 16 different bank groups.
+__device__ __forceinline__ int t128_off(int row, int col) {  // byte offset of element (row, col)
+    return row * 256 + ((((col >> 3) ^ row) & 15) << 4) + (col & 7) * 2;
+}
+
+// Transposing store: the workgroup copies a [rows_valid x 64] fp16 matrix M (row-major, leading dimension ld)
+// into T[64][128] with T[c][r] = M[r][c]; rows >= rows_valid become zero.
+__device__ __forceinline__ void stage_transposed(const uint16_t* M, int ld, int rows_valid, char* T) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int v = threadIdx.x + AT_THREADS * j;  // 1024 vectors of 8 columns
+        const int r = v >> 3, c0 = (v & 7) * 8;
+        const u32x4a q = load_row8(M, ld, r, rows_valid, c0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned w = q[e >> 1];
+            *reinterpret_cast<uint16_t*>(T + t128_off(c0 + e, r)) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
+        }
+    }
+}
+
+// Fragment of T for the "probability-ordered" k-set of (tile t, half-slice s): row = lane%32 (+ row0).
+__device__ __forceinline__ f16x8 t128_frag_pairs(const char* T, int row, int t, int s, int hf) {
+    const int     c  = 32 * t + 16 * s + 4 * hf;
+    const u32x2a  lo = *reinterpret_cast<const u32x2a*>(T + t128_off(row, c));
+    const u32x2a  hi = *reinterpret_cast<const u32x2a*>(T + t128_off(row, c + 8));
+    return join_f16x8(lo, hi);
+}
+// Fragment of T with 8 consecutive columns starting at 16 kk + 8 hf (the plain k-order).
+__device__ __forceinline__ f16x8 t128_frag(const char* T, int row, int kk, int hf) {
+    return as_f16x8(*reinterpret_cast<const u32x4a*>(T + t128_off(row, 16 * kk + 8 * hf)));
+}
+
+// scores / dP tile product for one wave: D[n][m] = sum_d Arows[n][d] * Brows[m][d], operands read straight
+// from global memory (head dimension contiguous), m = 32 wave + lane%32, n over four 32-key tiles.
+__device__ __forceinline__ void rows_product(const uint16_t* An, int lda, const uint16_t* Bm, int ldb, int S, int wave,
+                                             int lane, f32x16 (&acc)[4]) {
+    const int hf = lane >> 5, m = 32 * wave + (lane & 31);
+    f16x8     bq[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) bq[kk] = as_f16x8(load_row8(Bm, ldb, m, S, 16 * kk + 8 * hf));
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        acc[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (32 * t < S) {  // wave-uniform
+            const int n = 32 * t + (lane & 31);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const f16x8 ak = as_f16x8(load_row8(An, lda, n, S, 16 * kk + 8 * hf));
+                acc[t]         = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak, bq[kk], acc[t], 0, 0, 0);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------ forward
+__global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
+                                                                    int ld, int d_model, float alpha,
+                                                                    uint16_t* __restrict__ P, uint16_t* __restrict__ ctx,
+                                                                    int ld_ctx) {
+    extern __shared__ __align__(16) char smem[];  // Vt[64][128]
+    const int b = blockIdx.x / n_heads, h = blockIdx.x - b * n_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
+    const uint16_t* q = qkv + (long long)b * S * ld + h * AT_D;
+    const uint16_t* k = q + d_model;
+    const uint16_t* v = q + 2 * d_model;
+    uint16_t*       Pb = P + (long long)blockIdx.x * S * S;
+
+    stage_transposed(v, ld, S, smem);  // Vt[d][n]
+
+    f32x16 acc[4];
+    rows_product(k, ld, q, ld, S, wave, lane, acc);
+
+    // softmax over the keys of query m; a lane holds 64 of its 128 scores, lane^32 the others
+    const int m  = 32 * wave + (lane & 31);
+    float     mx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int   n = 32 * t + 8 * (r >> 2) + 4 * hf + (r & 3);
+            const float s = (n < S) ? round16(alpha * acc[t][r]) : -INFINITY;
+            acc[t][r]     = s;
+            mx            = fmaxf(mx, s);
+        }
+    mx        = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float e = __expf(acc[t][r] - mx);  // exp(-inf) = 0 for masked keys
+            acc[t][r]     = e;
+            sum += e;
+        }
+    sum += __shfl_xor(sum, 32, 64);
+    unsigned pk[4][8];  // probabilities as fp16 pairs: pk[t][2q], pk[t][2q+1] = keys 32t + 8q + 4hf + {0,1},{2,3}
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            pk[t][2 * qd]     = pack2(acc[t][4 * qd] / sum, acc[t][4 * qd + 1] / sum);
+            pk[t][2 * qd + 1] = pack2(acc[t][4 * qd + 2] / sum, acc[t][4 * qd + 3] / sum);
+            const int n       = 32 * t + 8 * qd + 4 * hf;
+            if (m < S && n < S) *reinterpret_cast<u32x2a*>(Pb + (long long)m * S + n) = u32x2a{pk[t][2 * qd], pk[t][2 * qd + 1]};
+        }
+    __syncthreads();  // Vt complete
+
+    // ctx[m][d] = sum_n p[m][n] v[n][d]: A = Vt rows d, B = probability registers
+    f32x16 o[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) {
+        o[dt] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (32 * t < S) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const f16x8 pv = as_f16x8(u32x4a{pk[t][4 * s], pk[t][4 * s + 1], pk[t][4 * s + 2], pk[t][4 * s + 3]});
+                    const f16x8 vt = t128_frag_pairs(smem, 32 * dt + (lane & 31), t, s, hf);
+                    o[dt]          = __builtin_amdgcn_mfma_f32_32x32x16_f16(vt, pv, o[dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (m < S) {
+        uint16_t* crow = ctx + ((long long)b * S + m) * ld_ctx + h * AT_D;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int d = 32 * dt + 8 * qd + 4 * hf;
+                *reinterpret_cast<u32x2a*>(crow + d) =
+                    u32x2a{pack2(o[dt][4 * qd], o[dt][4 * qd + 1]), pack2(o[dt][4 * qd + 2], o[dt][4 * qd + 3])};
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------ backward
+// LDS: Qt, Kt, dOt [64][128] (transposed copies) and Pt, dSt [128][128] (T[n][m]), 112 KiB.
+constexpr int AT_BWD_LDS = 3 * 64 * 256 + 2 * 128 * 256;
+
+__global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
+                                                                    int ld, int d_model, float alpha,
+                                                                    const uint16_t* __restrict__ P,
+                                                                    const uint16_t* __restrict__ dctx, int ld_ctx,
+                                                                    uint16_t* __restrict__ dqkv, int ld_dqkv) {
+    extern __shared__ __align__(16) char smem[];
+    char* Qt  = smem;
+    char* Kt  = Qt + 64 * 256;
+    char* dOt = Kt + 64 * 256;
+    char* Pt  = dOt + 64 * 256;
+    char* dSt = Pt + 128 * 256;
+    const int b = blockIdx.x / n_heads, h = blockIdx.x - b * n_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
+    const uint16_t* q  = qkv + (long long)b * S * ld + h * AT_D;
+    const uint16_t* k  = q + d_model;
+    const uint16_t* v  = q + 2 * d_model;
+    const uint16_t* dO = dctx + (long long)b * S * ld_ctx + h * AT_D;
+    const uint16_t* Pb = P + (long long)blockIdx.x * S * S;
+    uint16_t*       dq = dqkv + (long long)b * S * ld_dqkv + h * AT_D;
+    uint16_t*       dk = dq + d_model;
+    uint16_t*       dv = dq + 2 * d_model;
+
+    stage_transposed(q, ld, S, Qt);
+    stage_transposed(k, ld, S, Kt);
+    stage_transposed(dO, ld_ctx, S, dOt);
+
+    // dP[m][n] = sum_d dctx[m][d] v[n][d], same register layout as the scores (lane <-> query m)
+    f32x16 acc[4];
+    rows_product(v, ld, dO, ld_ctx, S, wave, lane, acc);
+
+    const int m = 32 * wave + (lane & 31);
+    float     pr[4][16];
+    float     inner = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int n = 32 * t + 8 * qd + 4 * hf;
+            u32x2a    w = u32x2a{0u, 0u};
+            if (m < S && n < S) w = *reinterpret_cast<const u32x2a*>(Pb + (long long)m * S + n);
+            pr[t][4 * qd]     = h2f((uint16_t)(w.x & 0xFFFFu));
+            pr[t][4 * qd + 1] = h2f((uint16_t)(w.x >> 16));
+            pr[t][4 * qd + 2] = h2f((uint16_t)(w.y & 0xFFFFu));
+            pr[t][4 * qd + 3] = h2f((uint16_t)(w.y >> 16));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float dp    = round16(acc[t][4 * qd + e]);  // dP is a stored tensor
+                acc[t][4 * qd + e] = dp;
+                inner += dp * pr[t][4 * qd + e];
+            }
+        }
+    inner += __shfl_xor(inner, 32, 64);
+    // dS = RNE16(p (dP - inner)); keep it as fp16 pairs, and scatter p and dS transposed into LDS (T[n][m])
+    unsigned ds[4][8];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            uint16_t hs[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int r = 4 * qd + e, n = 32 * t + 8 * qd + 4 * hf + e;
+                hs[e]       = f2h(pr[t][r] * (acc[t][r] - inner));
+                *reinterpret_cast<uint16_t*>(Pt + t128_off(n, m))  = f2h(pr[t][r]);
+                *reinterpret_cast<uint16_t*>(dSt + t128_off(n, m)) = hs[e];
+            }
+            ds[t][2 * qd]     = (unsigned)hs[0] | ((unsigned)hs[1] << 16);
+            ds[t][2 * qd + 1] = (unsigned)hs[2] | ((unsigned)hs[3] << 16);
+        }
+    __syncthreads();  // Qt, Kt, dOt, Pt, dSt complete
+
+    // dQ[m][d] = alpha sum_n dS[m][n] k[n][d]: A = Kt rows d (probability-ordered keys), B = dS registers
+    {
+        f32x16 o[2];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+            o[dt] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (32 * t < S) {
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const f16x8 dsf = as_f16x8(u32x4a{ds[t][4 * s], ds[t][4 * s + 1], ds[t][4 * s + 2], ds[t][4 * s + 3]});
+                        const f16x8 kt  = t128_frag_pairs(Kt, 32 * dt + (lane & 31), t, s, hf);
+                        o[dt]           = __builtin_amdgcn_mfma_f32_32x32x16_f16(kt, dsf, o[dt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        if (m < S) {
+            uint16_t* row = dq + (long long)m * ld_dqkv;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    const int d = 32 * dt + 8 * qd + 4 * hf;
+                    *reinterpret_cast<u32x2a*>(row + d) = u32x2a{pack2(alpha * o[dt][4 * qd], alpha * o[dt][4 * qd + 1]),
+                                                                 pack2(alpha * o[dt][4 * qd + 2], alpha * o[dt][4 * qd + 3])};
+                }
+        }
+    }
+    // dV[n][d] = sum_m p[m][n] dctx[m][d] and dK[n][d] = alpha sum_m dS[m][n] q[m][d] for the 32 keys n of this wave:
+    // A = dOt / Qt rows d, B = Pt / dSt rows n, contraction over queries m in plain order.
+    if (32 * wave < S) {
+        const int n = 32 * wave + (lane & 31);
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const char* At    = which == 0 ? dOt : Qt;
+            const char* Bt    = which == 0 ? Pt : dSt;
+            uint16_t*   out   = which == 0 ? dv : dk;
+            const float scale = which == 0 ? 1.0f : alpha;
+            f32x16      o[2];
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                o[dt] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    if (16 * kk < S) {
+                        const f16x8 a  = t128_frag(At, 32 * dt + (lane & 31), kk, hf);
+                        const f16x8 bb = t128_frag(Bt, n, kk, hf);
+                        o[dt]          = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bb, o[dt], 0, 0, 0);
+                    }
+                }
+            }
+            if (n < S) {
+                uint16_t* row = out + (long long)n * ld_dqkv;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        const int d = 32 * dt + 8 * qd + 4 * hf;
+                        *reinterpret_cast<u32x2a*>(row + d) = u32x2a{pack2(scale * o[dt][4 * qd], scale * o[dt][4 * qd + 1]),
+                                                                     pack2(scale * o[dt][4 * qd + 2], scale * o[dt][4 * qd + 3])};
+                    }
+            }
+        }
+    }
+}
+
+}  // namespace mp
+
+using namespace mp;
+
+static int attention_check(const char* who, int n_seq, int n_heads, int S, int d_head, const void* qkv, int ld,
+                           const void* p, const void* ctx, int ld_ctx) {
+    MP_REQUIRE(n_seq > 0 && n_heads > 0 && S > 0 && d_head > 0, "%s: bad shape", who);
+    MP_REQUIRE(qkv && p && ctx, "%s: NULL argument", who);
+    if (d_head != AT_D || S > AT_S || (S & 7) != 0) {
+        set_error("%s: the fused kernel needs head size %d and seq_len a multiple of 8 up to %d (got %d, %d); "
+                  "use the unfused chain of mp_gemm_* and mp_softmax_* calls instead", who, AT_D, AT_S, d_head, S);
+        return MP_E_UNSUPPORTED;
+    }
+    const int d_model = n_heads * d_head;
+    MP_REQUIRE(ld >= 3 * d_model && (ld & 7) == 0 && ld_ctx >= d_model && (ld_ctx & 7) == 0,
+               "%s: leading dimensions must cover the row and be multiples of 8", who);
+    MP_REQUIRE(aligned16(qkv) && aligned16(p) && aligned16(ctx), "%s: pointers must be 16-byte aligned", who);
+    MP_REQUIRE((long long)n_seq * n_heads < (1ll << 31), "%s: too many (sequence, head) pairs", who);
+    return MP_OK;
+}
+
+extern "C" int mp_attention_fwd(int n_seq, int n_heads, int seq_len, int d_head, const mp_half* qkv, int ld_qkv,
+                                float alpha, mp_half* p, mp_half* ctx, int ld_ctx, mp_stream stream) {
+    int rc = attention_check("mp_attention_fwd", n_seq, n_heads, seq_len, d_head, qkv, ld_qkv, p, ctx, ld_ctx);
+    if (rc) return rc;
+    hipLaunchKernelGGL(attention_fwd_kernel, dim3(n_seq * n_heads), dim3(AT_THREADS), 64 * 256, as_stream(stream), n_heads,
+                       seq_len, qkv, ld_qkv, n_heads * d_head, alpha, p, ctx, ld_ctx);
+    MP_LAUNCH_CHECK("mp_attention_fwd");
+    return MP_OK;
+}
+
+extern "C" int mp_attention_bwd(int n_seq, int n_heads, int seq_len, int d_head, const mp_half* qkv, int ld_qkv,
+                                float alpha, const mp_half* p, const mp_half* dctx, int ld_ctx, mp_half* dqkv,
+                                int ld_dqkv, mp_stream stream) {
+    int rc = attention_check("mp_attention_bwd", n_seq, n_heads, seq_len, d_head, qkv, ld_qkv, p, dctx, ld_ctx);
+    if (rc) return rc;
+    MP_REQUIRE(dqkv && aligned16(dqkv) && ld_dqkv >= 3 * n_heads * d_head && (ld_dqkv & 7) == 0,
+               "mp_attention_bwd: bad dqkv / ld_dqkv");
+    static std::once_flag once;
+    static hipError_t     attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_bwd_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, AT_BWD_LDS);
+    });
+    if (attr_err != hipSuccess) return hip_fail(attr_err, "mp_attention_bwd: hipFuncSetAttribute(LDS size)");
+    hipLaunchKernelGGL(attention_bwd_kernel, dim3(n_seq * n_heads), dim3(AT_THREADS), AT_BWD_LDS, as_stream(stream), n_heads,
+                       seq_len, qkv, ld_qkv, n_heads * d_head, alpha, p, dctx, ld_ctx, dqkv, ld_dqkv);
+    MP_LAUNCH_CHECK("mp_attention_bwd");
+    return MP_OK;
+}

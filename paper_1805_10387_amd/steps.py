@@ -153,12 +153,17 @@ class MLPStep(_StepBase):
 class TransformerStep(_StepBase):
     """Stack of post-LayerNorm encoder layers with an MSE loss on the last output (configs 2, 3)."""
 
-    def __init__(self, wl, masters=None, two_streams=False, **kw):
+    def __init__(self, wl, masters=None, two_streams=False, fused_attention=True, **kw):
         if masters is None:
             masters = {f"l{i}.{k}": v for i, lay in enumerate(wl.masters()) for k, v in lay.items()}
         super().__init__(masters, wl.opt, wl.scale, **kw)
         self.wl = wl
         self.two_streams = two_streams
+        dk_ = wl.d_model // wl.n_heads
+        # the fused attention kernels cover head size 64 and sequences up to 128 (multiple of 8); anything else
+        # runs the unfused chain of batched products and softmax kernels
+        self.fused_attention = fused_attention and dk_ == 64 and wl.seq_len <= 128 and wl.seq_len % 8 == 0
+        self.alpha = 1.0 / math.sqrt(dk_)
         self.side_stream = torch.cuda.Stream() if two_streams else None
         T, d, f, h, S, NB = wl.tokens, wl.d_model, wl.d_ff, wl.n_heads, wl.seq_len, wl.n_seq
         dk = d // h
@@ -202,10 +207,13 @@ class TransformerStep(_StepBase):
         for l, a in enumerate(self.act):
             p = f"l{l}."
             B.mp_gemm_fwd(self.d_qkv, x, w[p + "wqkv"], w[p + "bqkv"], None, a["qkv"])
-            B.mp_gemm_fwd(self.d_s, a["qkv"], a["qkv"][:, d:], None, None, a["p"])
-            self._t("s", l, a["p"])
-            B.mp_softmax_fwd(NB * h * S, S, a["p"], a["p"], S)
-            B.mp_gemm_fwd(self.d_c, a["p"], a["qkv"][:, 2 * d:], None, None, a["ctx"])
+            if self.fused_attention:
+                B.mp_attention_fwd(NB, h, S, d // h, a["qkv"], 3 * d, self.alpha, a["p"], a["ctx"], d)
+            else:
+                B.mp_gemm_fwd(self.d_s, a["qkv"], a["qkv"][:, d:], None, None, a["p"])
+                self._t("s", l, a["p"])
+                B.mp_softmax_fwd(NB * h * S, S, a["p"], a["p"], S)
+                B.mp_gemm_fwd(self.d_c, a["p"], a["qkv"][:, 2 * d:], None, None, a["ctx"])
             B.mp_gemm_fwd(self.d_o, a["ctx"], w[p + "wo"], w[p + "bo"], None, a["a"])
             B.mp_layernorm_fwd(T, d, x, a["a"], w[p + "ln1_g"], w[p + "ln1_b"], LN_EPS, a["y1"], a["mean1"], a["rstd1"])
             B.mp_gemm_fwd(self.d_f1, a["y1"], w[p + "w1"], w[p + "b1"], None, a["f"])
@@ -264,13 +272,16 @@ class TransformerStep(_StepBase):
             B.mp_gemm_bwd_dx(self.d_o, dz1, w[p + "wo"], self.dctx)
             self._t("dctx", l, self.dctx)
             # attention: dP = dctx V^T, dV = P^T dctx, dS = softmax', dQ = alpha dS K, dK = alpha dS^T Q
-            B.mp_gemm_bwd_dx(self.d_c, self.dctx, a["qkv"][:, 2 * d:], self.dp)
-            self._t("dp", l, self.dp)
-            B.mp_gemm_bwd_dw(self.d_c, self.dctx, a["p"], dqkv[:, 2 * d:], None, None, ws)
-            B.mp_softmax_bwd(NB * h * S, S, a["p"], self.dp, self.dp, S)
-            self._t("ds", l, self.dp)
-            B.mp_gemm_bwd_dx(self.d_s, self.dp, a["qkv"][:, d:], dqkv)
-            B.mp_gemm_bwd_dw(self.d_s, self.dp, a["qkv"], dqkv[:, d:], None, None, ws)
+            if self.fused_attention:
+                B.mp_attention_bwd(NB, h, S, d // h, a["qkv"], 3 * d, self.alpha, a["p"], self.dctx, d, dqkv, 3 * d)
+            else:
+                B.mp_gemm_bwd_dx(self.d_c, self.dctx, a["qkv"][:, 2 * d:], self.dp)
+                self._t("dp", l, self.dp)
+                B.mp_gemm_bwd_dw(self.d_c, self.dctx, a["p"], dqkv[:, 2 * d:], None, None, ws)
+                B.mp_softmax_bwd(NB * h * S, S, a["p"], self.dp, self.dp, S)
+                self._t("ds", l, self.dp)
+                B.mp_gemm_bwd_dx(self.d_s, self.dp, a["qkv"][:, d:], dqkv)
+                B.mp_gemm_bwd_dw(self.d_s, self.dp, a["qkv"], dqkv[:, d:], None, None, ws)
             self._t("dqkv", l, dqkv)
             fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_qkv, dqkv, x, g[p + "wqkv"], g[p + "bqkv"], st, wsx))
             B.mp_gemm_bwd_dx(self.d_qkv, dqkv, w[p + "wqkv"], dx, add=dz1, ld_aux=d)

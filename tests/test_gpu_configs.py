@@ -200,8 +200,11 @@ def op_level_transformer(step, wl, batch, tol=GRAD_TOL, layers=None):
             continue
         check(a["qkv"], L.linear_fwd(MIXED, x, w[p + "wqkv"], w[p + "bqkv"]), f"{l} qkv")
         q, k, v = heads(a["qkv"])
-        check(tr[("s", l)], MIXED.store(alpha * (q @ k.transpose(0, 1, 3, 2))), f"{l} scores")
-        check(a["p"], MIXED.store(L.softmax_rows(MIXED, tr[("s", l)])), f"{l} softmax")
+        if ("s", l) in tr:
+            check(tr[("s", l)], MIXED.store(alpha * (q @ k.transpose(0, 1, 3, 2))), f"{l} scores")
+            check(a["p"], MIXED.store(L.softmax_rows(MIXED, tr[("s", l)])), f"{l} softmax")
+        else:                                       # fused attention: scores never reach memory
+            check(a["p"], MIXED.store(L.softmax_rows(MIXED, MIXED.store(alpha * (q @ k.transpose(0, 1, 3, 2))))), f"{l} softmax(scores)")
         check(a["ctx"], L._unheads(MIXED.store(a["p"] @ v)), f"{l} ctx")
         check(a["a"], L.linear_fwd(MIXED, a["ctx"], w[p + "wo"], w[p + "bo"]), f"{l} attn out")
         y1, c1 = L.layernorm_fwd(MIXED, x, a["a"], w[p + "ln1_g"], w[p + "ln1_b"])
@@ -235,10 +238,15 @@ def op_level_transformer(step, wl, batch, tol=GRAD_TOL, layers=None):
         check(g[p + "wo"], dw, f"{l} dwo"); check(g[p + "bo"], db, f"{l} dbo"); check(tr[("dctx", l)], dctx, f"{l} dctx")
         q, k, v = heads(a["qkv"])
         dctx_h = L._heads(tr[("dctx", l)], NB, S, h)
-        check(tr[("dp", l)], MIXED.store(dctx_h @ v.transpose(0, 1, 3, 2)), f"{l} dp")
-        dpg, pg = tr[("dp", l)], a["p"]
-        check(tr[("ds", l)], MIXED.store(pg * (dpg - (dpg * pg).sum(-1, keepdims=True, dtype=np.float32))), f"{l} ds")
-        dsg = tr[("ds", l)]
+        pg = a["p"]
+        if ("dp", l) in tr:
+            check(tr[("dp", l)], MIXED.store(dctx_h @ v.transpose(0, 1, 3, 2)), f"{l} dp")
+            dpg = tr[("dp", l)]
+            check(tr[("ds", l)], MIXED.store(pg * (dpg - (dpg * pg).sum(-1, keepdims=True, dtype=np.float32))), f"{l} ds")
+            dsg = tr[("ds", l)]
+        else:                                       # fused attention: dP and dS stay on chip; follow the oracle's own
+            dpg = MIXED.store(dctx_h @ v.transpose(0, 1, 3, 2))
+            dsg = MIXED.store(pg * (dpg - (dpg * pg).sum(-1, keepdims=True, dtype=np.float32)))
         dqkv = np.concatenate([L._unheads(MIXED.store(alpha * (dsg @ k))),
                                L._unheads(MIXED.store(alpha * (dsg.transpose(0, 1, 3, 2) @ q))),
                                L._unheads(MIXED.store(pg.transpose(0, 1, 3, 2) @ dctx_h))], axis=1)
@@ -269,6 +277,16 @@ def test_config2_reduced_size():
 
 def test_config3_reduced_size_two_layers():
     _transformer(I.C3_SMALL, 3, 3)
+
+
+def test_unfused_attention_path_reduced_size():
+    """The chain of batched products and softmax kernels (used where the fused kernel does not apply)."""
+    wl = I.C3_SMALL
+    batch = wl.batch()
+    step = St.TransformerStep(wl, fused_attention=False)
+    step.set_batch(batch)
+    assert not step.fused_attention
+    op_level_transformer(step, wl, batch)
 
 
 def test_config3_reduced_prechecked_flat_update_matches_default():

@@ -151,6 +151,41 @@ def test_gemm_attention_batched_strided():
     assert_close16(dqkv_d, dqkv_ref, 1e-3, what="dqkv")
 
 
+@pytest.mark.parametrize("B,S,h", [(3, 128, 2), (2, 40, 3), (5, 64, 1), (1, 8, 4), (2, 104, 2)])
+def test_fused_attention_fwd_bwd(B, S, h):
+    dk = 64
+    d_model, T = h * dk, B * S
+    r = RNG(B * 1000 + S + h)
+    qkv = S16(r.standard_normal((T, 3 * d_model)))
+    ctx_ref, cache = L.attention_fwd(MIXED, qkv, B, S, h)
+    q, k, v, p_ref, alpha = cache
+    qkv_d = h16(qkv)
+    p_d = torch.zeros(B, h, S, S, dtype=torch.float16, device="cuda")
+    ctx_d = torch.full((T, d_model + 8), 3.0, dtype=torch.float16, device="cuda")
+    mp.mp_attention_fwd(B, h, S, dk, qkv_d, 3 * d_model, float(alpha), p_d, ctx_d, d_model + 8)
+    assert_close16(p_d, p_ref, 1e-3, max_ulp=2, what="fused p")
+    assert_close16(ctx_d[:, :d_model], ctx_ref, 1e-3, what="fused ctx")
+    assert torch.all(ctx_d[:, d_model:] == 3.0)
+    # backward from the GPU's own p (the stored tensor both sides would use)
+    dctx = S16(r.standard_normal((T, d_model)))
+    p_gpu = np32(p_d)
+    dqkv_ref = L.attention_bwd(MIXED, dctx, (q, k, v, p_gpu, alpha))
+    dqkv_d = torch.zeros(T, 3 * d_model, dtype=torch.float16, device="cuda")
+    mp.mp_attention_bwd(B, h, S, dk, qkv_d, 3 * d_model, float(alpha), p_d, h16(dctx), d_model, dqkv_d, 3 * d_model)
+    for name, lo in (("dq", 0), ("dk", d_model), ("dv", 2 * d_model)):
+        assert_close16(dqkv_d[:, lo:lo + d_model], dqkv_ref[:, lo:lo + d_model], 1e-3, what=f"fused {name}")
+
+
+def test_fused_attention_rejects_unsupported_shapes():
+    x = empty16(64, 3 * 96)
+    with pytest.raises(mp.MPError) as e:
+        mp.mp_attention_fwd(1, 2, 64, 48, x, 3 * 96, 0.1, empty16(1, 2, 64, 64), empty16(64, 96), 96)
+    assert e.value.code == ML.MP_E_UNSUPPORTED
+    x = empty16(36, 3 * 64)
+    with pytest.raises(mp.MPError):
+        mp.mp_attention_fwd(1, 1, 36, 64, x, 3 * 64, 0.1, empty16(1, 1, 36, 36), empty16(36, 64), 64)
+
+
 def test_gemm_overflow_gives_inf_and_dw_sets_flag():
     M, N, K = 64, 64, 64
     x = np.full((M, K), 200.0, np.float32)
