@@ -181,8 +181,9 @@ __global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, 
 }
 
 // ------------------------------------------------------------------------------------ backward
-// LDS: Qt, Kt, dOt [64][128] (transposed copies) and Pt, dSt [128][128] (T[n][m]), 112 KiB.
-constexpr int AT_BWD_LDS = 3 * 64 * 256 + 2 * 128 * 256;
+// LDS: Pt, dSt [128][128] (T[n][m]) plus one [64][128] buffer X that holds Kt for dQ, then dOt for dV, then Qt
+// for dK: 80 KiB, so two workgroups share a CU.
+constexpr int AT_BWD_LDS = 2 * 128 * 256 + 64 * 256;
 
 __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
                                                                     int ld, int d_model, float alpha,
@@ -190,11 +191,9 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
                                                                     const uint16_t* __restrict__ dctx, int ld_ctx,
                                                                     uint16_t* __restrict__ dqkv, int ld_dqkv) {
     extern __shared__ __align__(16) char smem[];
-    char* Qt  = smem;
-    char* Kt  = Qt + 64 * 256;
-    char* dOt = Kt + 64 * 256;
-    char* Pt  = dOt + 64 * 256;
+    char* Pt  = smem;
     char* dSt = Pt + 128 * 256;
+    char* X   = dSt + 128 * 256;
     const int b = blockIdx.x / n_heads, h = blockIdx.x - b * n_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
     const uint16_t* q  = qkv + (long long)b * S * ld + h * AT_D;
@@ -206,9 +205,7 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
     uint16_t*       dk = dq + d_model;
     uint16_t*       dv = dq + 2 * d_model;
 
-    stage_transposed(q, ld, S, Qt);
-    stage_transposed(k, ld, S, Kt);
-    stage_transposed(dO, ld_ctx, S, dOt);
+    stage_transposed(k, ld, S, X);  // Kt
 
     // dP[m][n] = sum_d dctx[m][d] v[n][d], same register layout as the scores (lane <-> query m)
     f32x16 acc[4];
@@ -253,7 +250,7 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
             ds[t][2 * qd]     = (unsigned)hs[0] | ((unsigned)hs[1] << 16);
             ds[t][2 * qd + 1] = (unsigned)hs[2] | ((unsigned)hs[3] << 16);
         }
-    __syncthreads();  // Qt, Kt, dOt, Pt, dSt complete
+    __syncthreads();  // Kt, Pt, dSt complete
 
     // dQ[m][d] = alpha sum_n dS[m][n] k[n][d]: A = Kt rows d (probability-ordered keys), B = dS registers
     {
@@ -267,7 +264,7 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
 #pragma unroll
                     for (int s = 0; s < 2; ++s) {
                         const f16x8 dsf = as_f16x8(u32x4a{ds[t][4 * s], ds[t][4 * s + 1], ds[t][4 * s + 2], ds[t][4 * s + 3]});
-                        const f16x8 kt  = t128_frag_pairs(Kt, 32 * dt + (lane & 31), t, s, hf);
+                        const f16x8 kt  = t128_frag_pairs(X, 32 * dt + (lane & 31), t, s, hf);
                         o[dt]           = __builtin_amdgcn_mfma_f32_32x32x16_f16(kt, dsf, o[dt], 0, 0, 0);
                     }
                 }
@@ -287,11 +284,13 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
     }
     // dV[n][d] = sum_m p[m][n] dctx[m][d] and dK[n][d] = alpha sum_m dS[m][n] q[m][d] for the 32 keys n of this wave:
     // A = dOt / Qt rows d, B = Pt / dSt rows n, contraction over queries m in plain order.
-    if (32 * wave < S) {
-        const int n = 32 * wave + (lane & 31);
+    const int n = 32 * wave + (lane & 31);
 #pragma unroll
-        for (int which = 0; which < 2; ++which) {
-            const char* At    = which == 0 ? dOt : Qt;
+    for (int which = 0; which < 2; ++which) {
+        __syncthreads();  // everyone is done reading X
+        stage_transposed(which == 0 ? dO : q, which == 0 ? ld_ctx : ld, S, X);  // dOt, then Qt
+        __syncthreads();
+        if (32 * wave < S) {  // wave-uniform
             const char* Bt    = which == 0 ? Pt : dSt;
             uint16_t*   out   = which == 0 ? dv : dk;
             const float scale = which == 0 ? 1.0f : alpha;
@@ -302,7 +301,7 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) {
                     if (16 * kk < S) {
-                        const f16x8 a  = t128_frag(At, 32 * dt + (lane & 31), kk, hf);
+                        const f16x8 a  = t128_frag(X, 32 * dt + (lane & 31), kk, hf);
                         const f16x8 bb = t128_frag(Bt, n, kk, hf);
                         o[dt]          = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bb, o[dt], 0, 0, 0);
                     }
