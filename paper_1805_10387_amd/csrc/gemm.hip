@@ -366,9 +366,112 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
     constexpr int RPP = 64 / LPR;                       // rows per pass
     const int     lr = lane / LPR, lc = (lane % LPR) * 8;
 
+    // per-lane constants of the epilogue: this lane's 8 output columns and their bias values
+    const int n_lane = n0 + wn * WN + lc;
+    float     bias8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bias8[e] = 0.f;
+    if (g.bias && (!EDGE || n_lane < g.N)) {
+        const u32x4 braw = load8_guard(g.bias + n_lane, EDGE ? g.N - n_lane : 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bias8[e] = h2f((uint16_t)((e & 1) ? (braw[e >> 1] >> 16) : (braw[e >> 1] & 0xFFFFu)));
+    }
+    constexpr int NP = 32 / RPP;  // passes per slab
+
+    // one pass: row r of the current slab, this lane's 8 columns; `araw` = the 8 fp16 values of the ReLU
+    // source / residual operand at the same place (zero when there is none)
+    auto emit = [&](int i, int ps, u32x4 araw) {
+        const int r = ps * RPP + lr;
+        const int m = m0 + wm * WM + i * 32 + r;
+        const int n = n_lane;
+        if (EDGE && (m >= g.M || n >= g.N)) return;
+        const f32x4 s0 = *reinterpret_cast<const f32x4*>(slab + r * SLD + lc);
+        const f32x4 s1 = *reinterpret_cast<const f32x4*>(slab + r * SLD + lc + 4);
+        float       v[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+        const bool  full = !EDGE || n + 8 <= g.N;
+        const long long mn = (long long)m * g.N + n;
+        if (C32) {  // raw accumulator out: split-K partial, or fp32 result with alpha and addend
+            if (!split) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] *= g.alpha;
+                if (g.acc_in) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (full || n + e < g.N) v[e] += g.acc_in[mn + e];
+                }
+            }
+            if (full) {
+                *reinterpret_cast<float4*>(C32 + mn)     = make_float4(v[0], v[1], v[2], v[3]);
+                *reinterpret_cast<float4*>(C32 + mn + 4) = make_float4(v[4], v[5], v[6], v[7]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < g.N) C32[mn + e] = v[e];
+            }
+            return;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= g.alpha;
+        if (g.acc_in) {
+            if (full) {
+                const float4 t0 = *reinterpret_cast<const float4*>(g.acc_in + mn);
+                const float4 t1 = *reinterpret_cast<const float4*>(g.acc_in + mn + 4);
+                v[0] += t0.x; v[1] += t0.y; v[2] += t0.z; v[3] += t0.w;
+                v[4] += t1.x; v[5] += t1.y; v[6] += t1.z; v[7] += t1.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < g.N) v[e] += g.acc_in[mn + e];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += bias8[e];
+        if (g.relu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+        }
+        uint16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = f2h(v[e]);
+        if (aux) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float t = h2f((uint16_t)((e & 1) ? (araw[e >> 1] >> 16) : (araw[e >> 1] & 0xFFFFu)));
+                if (g.relu_src) {
+                    if (!(t > 0.f)) h[e] = 0;
+                } else {
+                    h[e] = f2h(h2f(h[e]) + t);
+                }
+            }
+        }
+        if (g.found_inf) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) bad |= (full || n + e < g.N) && half_nonfinite(h[e]);
+        }
+        uint16_t* dst = C + (long long)m * g.ldc + n;
+        if (full) {
+            *reinterpret_cast<u32x4*>(dst) = u32x4{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
+                                                   (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16)};
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n + e < g.N) dst[e] = h[e];
+        }
+    };
+
+    // Slabs are private to a wave and LDS operations of one wave execute in order, so no workgroup barrier is
+    // needed between writing a slab and reading it back (the main loop ended with one).
     static_for<TM>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
-        __syncthreads();  // previous slab fully read (and, first time, main-loop LDS reads done)
+        u32x4 av[NP];
+        if constexpr (!EDGE) {
+            // all residual / ReLU-source loads of this slab are issued before the LDS round trip
+#pragma unroll
+            for (int ps = 0; ps < NP; ++ps) {
+                av[ps] = u32x4{0u, 0u, 0u, 0u};
+                if (aux) av[ps] = *reinterpret_cast<const u32x4*>(aux + (long long)(m0 + wm * WM + i * 32 + ps * RPP + lr) * g.ld_aux + n_lane);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -376,93 +479,22 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
                 const f32x4 v = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
                 *reinterpret_cast<f32x4*>(slab + (lane & 31) * SLD + j * 32 + q * 8 + (lane >> 5) * 4) = v;
             }
-        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if constexpr (!EDGE) {
+#pragma unroll
+            for (int ps = 0; ps < NP; ++ps) emit(i, ps, av[ps]);
+        } else {
 #pragma unroll 1
-        for (int ps = 0; ps < 32 / RPP; ++ps) {
-            const int r = ps * RPP + lr;
-            const int m = m0 + wm * WM + i * 32 + r;
-            const int n = n0 + wn * WN + lc;
-            if (EDGE && (m >= g.M || n >= g.N)) continue;
-            const f32x4 s0 = *reinterpret_cast<const f32x4*>(slab + r * SLD + lc);
-            const f32x4 s1 = *reinterpret_cast<const f32x4*>(slab + r * SLD + lc + 4);
-            float       v[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
-            const bool  full = !EDGE || n + 8 <= g.N;
-            const long long mn = (long long)m * g.N + n;
-            if (C32) {  // raw accumulator out: split-K partial, or fp32 result with alpha and addend
-                if (!split) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] *= g.alpha;
-                    if (g.acc_in) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (full || n + e < g.N) v[e] += g.acc_in[mn + e];
-                    }
-                }
-                if (full) {
-                    *reinterpret_cast<float4*>(C32 + mn)     = make_float4(v[0], v[1], v[2], v[3]);
-                    *reinterpret_cast<float4*>(C32 + mn + 4) = make_float4(v[4], v[5], v[6], v[7]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (n + e < g.N) C32[mn + e] = v[e];
-                }
-                continue;
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] *= g.alpha;
-            if (g.acc_in) {
-                if (full) {
-                    const float4 t0 = *reinterpret_cast<const float4*>(g.acc_in + mn);
-                    const float4 t1 = *reinterpret_cast<const float4*>(g.acc_in + mn + 4);
-                    v[0] += t0.x; v[1] += t0.y; v[2] += t0.z; v[3] += t0.w;
-                    v[4] += t1.x; v[5] += t1.y; v[6] += t1.z; v[7] += t1.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (n + e < g.N) v[e] += g.acc_in[mn + e];
-                }
-            }
-            if (g.bias) {
-                const u32x4 braw = load8_guard(g.bias + n, g.N - n);
-                const unsigned bw[4] = {braw.x, braw.y, braw.z, braw.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] += h2f((uint16_t)((e & 1) ? (bw[e >> 1] >> 16) : (bw[e >> 1] & 0xFFFF)));
-            }
-            if (g.relu) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
-            }
-            uint16_t h[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = f2h(v[e]);
-            if (aux) {
-                const u32x4 araw = load8_guard(aux + (long long)m * g.ld_aux + n, g.N - n);
-                const unsigned aw[4] = {araw.x, araw.y, araw.z, araw.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float t = h2f((uint16_t)((e & 1) ? (aw[e >> 1] >> 16) : (aw[e >> 1] & 0xFFFF)));
-                    if (g.relu_src) {
-                        if (!(t > 0.f)) h[e] = 0;
-                    } else {
-                        h[e] = f2h(h2f(h[e]) + t);
-                    }
-                }
-            }
-            if (g.found_inf) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) bad |= (full || n + e < g.N) && half_nonfinite(h[e]);
-            }
-            uint16_t* dst = C + (long long)m * g.ldc + n;
-            if (full) {
-                *reinterpret_cast<uint4*>(dst) =
-                    make_uint4((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
-                               (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16));
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (n + e < g.N) dst[e] = h[e];
+            for (int ps = 0; ps < NP; ++ps) {
+                u32x4     araw = u32x4{0u, 0u, 0u, 0u};
+                const int m    = m0 + wm * WM + i * 32 + ps * RPP + lr;
+                if (aux && m < g.M && n_lane < g.N) araw = load8_guard(aux + (long long)m * g.ld_aux + n_lane, g.N - n_lane);
+                emit(i, ps, araw);
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     });
     if (g.found_inf && __any(bad)) {
         if (lane == 0) atomicOr(g.found_inf, 1);
