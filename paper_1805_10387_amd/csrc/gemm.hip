@@ -200,12 +200,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
 
     extern __shared__ __align__(16) char smem[];
 
-    // ---- which tile: spread consecutive workgroup ids (round-robin over the 8 XCDs) so that each
-    // XCD works on a contiguous run of tiles, then walk tiles in bands of GROUP tile-rows.
-    const int nb  = gridDim.x;
-    int       pid = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int bo = blockIdx.y / g.batch_inner, bi = blockIdx.y - bo * g.batch_inner;
+    const uint16_t* A = g.A + bo * g.sa_o + bi * g.sa_i;
+    const uint16_t* B = g.B + bo * g.sb_o + bi * g.sb_i;
+    const int kbeg = blockIdx.z * g.k_per_split;
+    const int kend = min(g.K, kbeg + g.k_per_split);
+    const int nkt  = (kend - kbeg + BK - 1) / BK;
+    bool      bad  = false;
+
+    // ---- persistent over tiles: workgroup w takes tiles w, w + gridDim.x, ...  The stores of one tile's
+    // epilogue drain while the next tile's first loads are in flight.
+    const int ntiles = g.tiles_m * g.tiles_n;
+    for (int vb = blockIdx.x; vb < ntiles; vb += gridDim.x) {
+    // which tile: consecutive ids are dispatched round-robin over the 8 XCDs (gridDim.x is a multiple of 8
+    // whenever a workgroup takes more than one tile), so id -> (id % 8) * (ntiles / 8) + id / 8 gives each XCD
+    // a contiguous run of tiles; tiles are then walked in bands of GROUP tile-rows.
+    int pid = vb;
     {
-        const int q = nb >> 3, rem = nb & 7, x = pid & 7, local = pid >> 3;
+        const int q = ntiles >> 3, rem = ntiles & 7, x = pid & 7, local = pid >> 3;
         pid = x * q + min(x, rem) + local;
     }
     constexpr int GROUP = 4;
@@ -217,16 +231,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
     const int     tile_n = inb / gsz;
     const int     m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int bo = blockIdx.y / g.batch_inner, bi = blockIdx.y - bo * g.batch_inner;
-    const uint16_t* A = g.A + bo * g.sa_o + bi * g.sa_i;
-    const uint16_t* B = g.B + bo * g.sb_o + bi * g.sb_i;
-
-    const int kbeg = blockIdx.z * g.k_per_split;
-    const int kend = min(g.K, kbeg + g.k_per_split);
-    const int nkt  = (kend - kbeg + BK - 1) / BK;
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -358,7 +362,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
     if (aux) aux += bo * g.sc_o + bi * g.sc_i;
     float*     C32   = g.C32 ? g.C32 + (long long)blockIdx.z * g.M * g.N : nullptr;
     const bool split = gridDim.z > 1;
-    bool       bad   = false;
 
     constexpr int SLD = WN + 4;                         // slab row stride in floats (pad: conflict-free)
     float*        slab = reinterpret_cast<float*>(smem) + wave * (32 * SLD);
@@ -496,6 +499,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     });
+    __syncthreads();  // every wave is done with its slab before the next tile's loads overwrite the LDS stages
+    }  // tile loop
     if (g.found_inf && __any(bad)) {
         if (lane == 0) atomicOr(g.found_inf, 1);
     }
@@ -681,7 +686,14 @@ static int run_gemm(GemmArgs g, bool a_kc, bool b_kc, long long batches, bool al
     g.k_per_split = p.k_per_split;
     g.tiles_m     = (g.M + kTiles[p.tile].bm - 1) / kTiles[p.tile].bm;
     g.tiles_n     = (g.N + kTiles[p.tile].bn - 1) / kTiles[p.tile].bn;
-    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n), (unsigned)batches, (unsigned)p.splits);
+    // persistent along x: at most as many workgroups as fit on the chip at once (a multiple of 8, see the tile
+    // mapping); batches and splits keep their own grid dimensions
+    const int  ntiles   = g.tiles_m * g.tiles_n;
+    const int  lds_kib  = 2 * (kTiles[p.tile].bm + kTiles[p.tile].bn) * 128 / 1024;
+    const int  resident = kCUs * (lds_kib > 80 ? 1 : 2);
+    const long long others = batches * p.splits;
+    const int  gx = (others == 1 && ntiles > resident) ? resident : ntiles;
+    const dim3 grid((unsigned)gx, (unsigned)batches, (unsigned)p.splits);
 
     GemmArgs k = g;
     if (p.splits > 1) {  // partials to workspace, epilogue in the finish kernel
