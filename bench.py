@@ -27,6 +27,12 @@ sys.path.insert(0, ROOT)
 PEAK_FP16_TFLOPS = 2500.0   # MI355X dense fp16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch from the rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, each scaled by
+# what the same counter reads for the 256 MiB calibration copy below); the summaries with the commands are
+# profiles/gemm_update_config3_hbm_traffic.txt.  None until measured.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = None
+UPDATE_TRAFFIC_BYTES_PER_LAUNCH = None
+
 
 def _time_calls(torch, fn, reps):
     """Average duration (s) of fn() launched reps times back to back on the current stream."""
@@ -72,6 +78,48 @@ def gemm_roofline(torch, B, step, reps=20):
     return flops, secs, per
 
 
+class GemmTimer:
+    """Brackets every dense-contraction call the step makes (mp_gemm_fwd / mp_gemm_bwd_dx / mp_gemm_bwd_dw)
+    with a pair of events on the launch stream while the step runs eagerly, so each launch is timed where it
+    runs in the step: same operands, same cache state, same neighbours.  flops = 2 M N K x batches."""
+
+    NAMES = ("mp_gemm_fwd", "mp_gemm_bwd_dx", "mp_gemm_bwd_dw")
+
+    def __init__(self, torch, B):
+        self.torch, self.B, self.saved, self.rec = torch, B, {}, []
+
+    def __enter__(self):
+        for name in self.NAMES:
+            fn = getattr(self.B, name)
+            self.saved[name] = fn
+
+            def timed(desc, *a, _fn=fn, **kw):
+                e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+                e0.record()
+                r = _fn(desc, *a, **kw)
+                e1.record()
+                fl = 2.0 * desc.M * desc.N * desc.K * max(desc.batch_outer, 1) * max(desc.batch_inner, 1)
+                byts = 2.0 * (desc.M * desc.K + desc.K * desc.N + desc.M * desc.N) * max(desc.batch_outer, 1) * max(desc.batch_inner, 1)
+                # an empty bracket right behind it: what two event records cost on this stream with nothing between
+                z0, z1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+                z0.record()
+                z1.record()
+                self.rec.append((e0, e1, fl, byts, z0, z1))
+                return r
+            setattr(self.B, name, timed)
+        return self
+
+    def __exit__(self, *exc):
+        for name, fn in self.saved.items():
+            setattr(self.B, name, fn)
+
+    def totals(self):
+        self.torch.cuda.synchronize()
+        raw = sum(r[0].elapsed_time(r[1]) for r in self.rec) * 1e-3
+        empty = sum(r[4].elapsed_time(r[5]) for r in self.rec) * 1e-3
+        return len(self.rec), sum(r[2] for r in self.rec), sum(r[3] for r in self.rec), raw, empty
+
+
 def cpu_baseline(wl, seconds_hint=20.0):
     """The oracle, as it stands, on a bounded sample of config 3: all 6 layers at full width, 16 of the 64
     sequences (2048 of 8192 tokens), complete iterations (forward, loss, backward, Adam on masters)."""
@@ -106,6 +154,7 @@ def main():
     ap.add_argument("--two-streams", action="store_true", help="enqueue the weight-gradient products on a second stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--insitu-steps", type=int, default=3, help="eager steps whose contractions are timed one by one")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
@@ -146,8 +195,16 @@ def main():
     st = step.state()
     loss = float(step.loss)
 
-    # ---- roofline of the dominant kernels, timed live with events on the launch stream
-    flops, secs, per = gemm_roofline(torch, B, step)
+    # ---- roofline of the dominant kernel, timed live with events on the launch stream: every dense
+    # contraction of the step, bracketed where it runs (eager launches of the same step, same buffers)
+    step.step()
+    with GemmTimer(torch, B) as gt:
+        for _ in range(args.insitu_steps):
+            step.step()
+    n_launch, flops, gemm_bytes, raw_secs, empty_secs = gt.totals()
+    secs = raw_secs - empty_secs                  # bracket minus empty bracket = the launches themselves
+    # the 12 distinct contractions of one layer again, each alone and back to back (operands warm in L2)
+    iso_flops, iso_secs, per = gemm_roofline(torch, B, step)
     n_params = step.P.total                       # elements the flat update descriptor covers
     upd_bytes = 28.0 * n_params
     t_upd = _time_calls(torch, lambda: B.mp_unscale_check_update(step.P.flat_list, 1, step.cfg, step.st, 1), 10)
@@ -174,13 +231,18 @@ def main():
         "step_gemm_tflops": wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12,
         "step_mfma_util_pct": 100.0 * wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12 / PEAK_FP16_TFLOPS,
         "final_loss": loss, "loss_scale": st.scale, "opt_steps": st.opt_step, "skipped": st.skipped_steps,
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (dense fp16 contractions of one layer: 4 fwd, 4 dX, 4 dW)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (every dense fp16 contraction of the step: per layer 4 fwd, 4 dX, 4 dW)",
                      "achieved": flops / secs * 1e-12, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops / secs * 1e-12 / PEAK_FP16_TFLOPS, "traffic": None,
-                     "flops_per_launch_set": flops, "per_call": per},
+                     "frac": flops / secs * 1e-12 / PEAK_FP16_TFLOPS,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+                     "launches_timed": n_launch, "launches_per_step": n_launch // max(args.insitu_steps, 1),
+                     "avg_launch_us": secs / n_launch * 1e6, "avg_bracket_us": raw_secs / n_launch * 1e6,
+                     "avg_empty_bracket_us": empty_secs / n_launch * 1e6, "flops_per_launch": flops / n_launch,
+                     "algorithmic_bytes_per_launch": gemm_bytes / n_launch,
+                     "isolated": {"achieved": iso_flops / iso_secs * 1e-12, "per_call": per}},
         "roofline_update": {"bound": "hbm", "kernel": "update_kernel<ADAM> (unscale + Adam + fp16 re-cast)",
                             "achieved": upd_bytes / t_upd * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                            "frac": upd_bytes / t_upd * 1e-9 / PEAK_HBM_GBS, "traffic": None,
+                            "frac": upd_bytes / t_upd * 1e-9 / PEAK_HBM_GBS, "traffic": UPDATE_TRAFFIC_BYTES_PER_LAUNCH,
                             "bytes_per_launch": upd_bytes, "us": t_upd * 1e6,
                             "with_inspection_pass_us": t_upd_chk * 1e6,
                             "with_inspection_pass_GBs": (upd_bytes + 2.0 * n_params) / t_upd_chk * 1e-9},

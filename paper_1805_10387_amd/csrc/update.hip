@@ -78,9 +78,11 @@ __global__ void loss_scale_update_kernel(mp_scale_state* st) {
 
 // ------------------------------------------------------------------ multi-tensor update
 constexpr int UPD_THREADS     = 256;
-constexpr int UPD_VEC         = 8;                                  // elements per lane per access
-constexpr int UPD_ITERS       = 4;
+constexpr int UPD_VEC         = 4;                                  // elements per lane per access
+constexpr int UPD_ITERS       = 8;
 constexpr int UPD_CHUNK       = UPD_THREADS * UPD_VEC * UPD_ITERS;  // 8192 elements per workgroup
+constexpr int INS_VEC         = 8;                                  // the inspection pass reads fp16 only: 16 B per lane
+constexpr int INS_ITERS       = UPD_CHUNK / (UPD_THREADS * INS_VEC);
 constexpr int UPD_MAX_TENSORS = 32;                                 // descriptors per launch
 
 struct UpdBatch {
@@ -115,9 +117,9 @@ __global__ __launch_bounds__(UPD_THREADS) void inspect_kernel(UpdBatch b, mp_sca
     const bool                vec = (b.vec_ok >> t) & 1u;
     bool                      bad = false;
 #pragma unroll
-    for (int it = 0; it < UPD_ITERS; ++it) {
-        const unsigned long long i = off + (unsigned long long)(it * UPD_THREADS + threadIdx.x) * UPD_VEC;
-        if (vec && i + UPD_VEC <= n) {
+    for (int it = 0; it < INS_ITERS; ++it) {
+        const unsigned long long i = off + (unsigned long long)(it * UPD_THREADS + threadIdx.x) * INS_VEC;
+        if (vec && i + INS_VEC <= n) {
             const uint4 q = *reinterpret_cast<const uint4*>(g + i);
             // both halves of each 32-bit word: exponent field 0x7C00 all ones
             const unsigned w[4] = {q.x, q.y, q.z, q.w};
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(UPD_THREADS) void inspect_kernel(UpdBatch b, mp_sca
                 bad |= ((w[k] & 0x7C00u) == 0x7C00u) | ((w[k] & 0x7C000000u) == 0x7C000000u);
             }
         } else {
-            for (unsigned long long j = i; j < n && j < i + UPD_VEC; ++j) bad |= half_nonfinite(g[j]);
+            for (unsigned long long j = i; j < n && j < i + INS_VEC; ++j) bad |= half_nonfinite(g[j]);
         }
     }
     if (__any(bad)) {
@@ -160,6 +162,9 @@ __device__ __forceinline__ void update_one(float g16v, float& w, float& m, float
     }
 }
 
+typedef float    f32x4v __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2v __attribute__((ext_vector_type(2)));
+
 template <int KIND>
 __global__ __launch_bounds__(UPD_THREADS) void update_kernel(UpdBatch b, UpdScalars s, const mp_scale_state* st) {
     if (st->found_inf != 0) return;  // overflow somewhere in this iteration: the whole step is skipped
@@ -180,49 +185,39 @@ __global__ __launch_bounds__(UPD_THREADS) void update_kernel(UpdBatch b, UpdScal
     float* __restrict__          vv  = b.v[t];
     const bool                   vec = (b.vec_ok >> t) & 1u;
 
+    // every access instruction of a wave covers one contiguous run (64 lanes x 16 B of fp32, 64 x 8 B of fp16),
+    // so each 128-byte line is touched by exactly one load and one store per array
 #pragma unroll
     for (int it = 0; it < UPD_ITERS; ++it) {
         const unsigned long long i = off + (unsigned long long)(it * UPD_THREADS + threadIdx.x) * UPD_VEC;
         if (vec && i + UPD_VEC <= n) {
-            const uint4 gq = *reinterpret_cast<const uint4*>(g16 + i);
-            float4      w0 = *reinterpret_cast<const float4*>(w32 + i);
-            float4      w1 = *reinterpret_cast<const float4*>(w32 + i + 4);
-            float4      m0 = make_float4(0, 0, 0, 0), m1 = m0, v0 = m0, v1 = m0;
+            // streaming data, touched once per step: non-temporal accesses keep it from displacing cache contents
+            const u32x2v gq = __builtin_nontemporal_load(reinterpret_cast<const u32x2v*>(g16 + i));
+            f32x4v       w0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4v*>(w32 + i));
+            f32x4v       m0 = {0.f, 0.f, 0.f, 0.f}, v0 = m0;
             if (KIND == MP_OPT_ADAM) {
-                m0 = *reinterpret_cast<const float4*>(mm + i);
-                m1 = *reinterpret_cast<const float4*>(mm + i + 4);
-                v0 = *reinterpret_cast<const float4*>(vv + i);
-                v1 = *reinterpret_cast<const float4*>(vv + i + 4);
+                m0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4v*>(mm + i));
+                v0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4v*>(vv + i));
             }
-            const unsigned gw[4] = {gq.x, gq.y, gq.z, gq.w};
-            float          g[8];
+            const float gh[4] = {h2f((uint16_t)(gq.x & 0xFFFFu)), h2f((uint16_t)(gq.x >> 16)),
+                                 h2f((uint16_t)(gq.y & 0xFFFFu)), h2f((uint16_t)(gq.y >> 16))};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                g[2 * k]     = h2f((uint16_t)(gw[k] & 0xFFFFu));
-                g[2 * k + 1] = h2f((uint16_t)(gw[k] >> 16));
+                float w = w0[k], m = m0[k], v = v0[k];
+                update_one<KIND>(gh[k], w, m, v, s, inv_scale, bc1, bc2);
+                w0[k] = w;
+                m0[k] = m;
+                v0[k] = v;
             }
-            update_one<KIND>(g[0], w0.x, m0.x, v0.x, s, inv_scale, bc1, bc2);
-            update_one<KIND>(g[1], w0.y, m0.y, v0.y, s, inv_scale, bc1, bc2);
-            update_one<KIND>(g[2], w0.z, m0.z, v0.z, s, inv_scale, bc1, bc2);
-            update_one<KIND>(g[3], w0.w, m0.w, v0.w, s, inv_scale, bc1, bc2);
-            update_one<KIND>(g[4], w1.x, m1.x, v1.x, s, inv_scale, bc1, bc2);
-            update_one<KIND>(g[5], w1.y, m1.y, v1.y, s, inv_scale, bc1, bc2);
-            update_one<KIND>(g[6], w1.z, m1.z, v1.z, s, inv_scale, bc1, bc2);
-            update_one<KIND>(g[7], w1.w, m1.w, v1.w, s, inv_scale, bc1, bc2);
-            *reinterpret_cast<float4*>(w32 + i)     = w0;
-            *reinterpret_cast<float4*>(w32 + i + 4) = w1;
+            __builtin_nontemporal_store(w0, reinterpret_cast<f32x4v*>(w32 + i));
             if (KIND == MP_OPT_ADAM) {
-                *reinterpret_cast<float4*>(mm + i)     = m0;
-                *reinterpret_cast<float4*>(mm + i + 4) = m1;
-                *reinterpret_cast<float4*>(vv + i)     = v0;
-                *reinterpret_cast<float4*>(vv + i + 4) = v1;
+                __builtin_nontemporal_store(m0, reinterpret_cast<f32x4v*>(mm + i));
+                __builtin_nontemporal_store(v0, reinterpret_cast<f32x4v*>(vv + i));
             }
-            uint4 hq;
+            u32x2v hq;
             hq.x = (unsigned)f2h(w0.x) | ((unsigned)f2h(w0.y) << 16);
             hq.y = (unsigned)f2h(w0.z) | ((unsigned)f2h(w0.w) << 16);
-            hq.z = (unsigned)f2h(w1.x) | ((unsigned)f2h(w1.y) << 16);
-            hq.w = (unsigned)f2h(w1.z) | ((unsigned)f2h(w1.w) << 16);
-            *reinterpret_cast<uint4*>(w16 + i) = hq;
+            *reinterpret_cast<u32x2v*>(w16 + i) = hq;  // read again by the next forward pass: ordinary store
         } else {
             for (unsigned long long j = i; j < n && j < i + UPD_VEC; ++j) {
                 float w = w32[j], m1 = 0.f, v1 = 0.f;
