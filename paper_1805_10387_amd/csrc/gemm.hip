@@ -61,6 +61,19 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
+// One accumulator register read / written where the statement stands.  The accumulators live in the AGPR half of the
+// register file; left to itself the compiler copies the whole set into VGPRs ahead of the epilogue's first branch.
+__device__ __forceinline__ float acc_get(float a) {
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+__device__ __forceinline__ float acc_put(float v) {
+    float a;
+    asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a) : "v"(v));
+    return a;
+}
+
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
 // 16-byte global load of 8 halves starting at p[0], of which only the first `valid` (0..8) exist.
@@ -232,11 +245,31 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
     const int     m0 = tile_m * BM, n0 = tile_n * BN;
 
 
-    f32x16 acc[TM][TN];
+    // The bias is a per-column constant of the fp32 sum, so it can start the accumulators (acc[i][j][4 q + c] is
+    // column 32 j + 8 q + 4 (lane / 32) + c of the wave tile); not when a scale factor follows the sum.
+    const int  er = lane & 31, eh = lane >> 5;
+    const int  ncol = n0 + wn * WN;
+    const bool fold_bias = g.bias != nullptr && g.C32 == nullptr && g.alpha == 1.f;
+    f32x16     acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (fold_bias) {
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        static_for<TN * 4>([&](auto tc) {
+            constexpr int t = decltype(tc)::value, j = t / 4, q = t % 4;
+            const int     n = ncol + 32 * j + 8 * q + 4 * eh;  // 4 consecutive columns: one 8-byte load
+            u32x2         braw = {0u, 0u};
+            if (!EDGE || n < g.N) braw = *reinterpret_cast<const u32x2*>(g.bias + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float b = h2f((uint16_t)((e & 1) ? (braw[e >> 1] >> 16) : (braw[e >> 1] & 0xFFFFu)));
+#pragma unroll
+                for (int i = 0; i < TM; ++i) acc[i][j][4 * q + e] = acc_put(b);
+            }
+        });
+    }
 
     // Two register sets per operand: the global loads of k-tile t+2 are issued before the matrix-core
     // work of tile t and are first needed (for the LDS store) after the work of tile t+1, so a load has
@@ -354,152 +387,135 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
     }
     if (kt < nkt) step(la0, lb0, la1, lb1, smem, smem + STAGE);  // odd tile count
 
-    // ---- epilogue.  Accumulators go through LDS (per wave, one 32-row slab at a time, fp32) so that
-    // global memory sees whole rows: each lane then owns 8 consecutive columns of one row and moves
-    // 16 bytes per access (bias, residual / ReLU-source loads and the fp16 store; 2 x 16 bytes for fp32).
+    // ---- epilogue, in the layout the matrix cores leave the result in.  Of the 32x32 tile (i, j) lane
+    // (er = lane % 32, eh = lane / 32) holds row er and, for q = 0..3, the 4 consecutive columns 8 q + 4 eh ...
+    // (acc[i][j][4 q + c]).  fp32 outputs are stored from there, 16 bytes per lane.  fp16 outputs are converted
+    // and packed in pairs, then lanes er and er + 32 trade halves (one cross-half register swap per packed pair)
+    // so that each lane ends up with 8 consecutive columns: 16-byte stores, and 16-byte loads of the residual /
+    // ReLU-source operand, without a trip through LDS.
+    asm volatile("s_nop 15\n\ts_nop 15");  // the last matrix-core results have landed before the explicit accumulator reads
     uint16_t*       C   = g.C ? g.C + bo * g.sc_o + bi * g.sc_i : nullptr;
     const uint16_t* aux = g.relu_src ? g.relu_src : g.add;
     if (aux) aux += bo * g.sc_o + bi * g.sc_i;
     float*     C32   = g.C32 ? g.C32 + (long long)blockIdx.z * g.M * g.N : nullptr;
     const bool split = gridDim.z > 1;
+    const int  mrow = m0 + wm * WM + er;  // + 32 i
 
-    constexpr int SLD = WN + 4;                         // slab row stride in floats (pad: conflict-free)
-    float*        slab = reinterpret_cast<float*>(smem) + wave * (32 * SLD);
-    constexpr int LPR = WN / 8;                         // lanes per slab row
-    constexpr int RPP = 64 / LPR;                       // rows per pass
-    const int     lr = lane / LPR, lc = (lane % LPR) * 8;
-
-    // per-lane constants of the epilogue: this lane's 8 output columns and their bias values
-    const int n_lane = n0 + wn * WN + lc;
-    float     bias8[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) bias8[e] = 0.f;
-    if (g.bias && (!EDGE || n_lane < g.N)) {
-        const u32x4 braw = load8_guard(g.bias + n_lane, EDGE ? g.N - n_lane : 8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) bias8[e] = h2f((uint16_t)((e & 1) ? (braw[e >> 1] >> 16) : (braw[e >> 1] & 0xFFFFu)));
-    }
-    constexpr int NP = 32 / RPP;  // passes per slab
-
-    // one pass: row r of the current slab, this lane's 8 columns; `araw` = the 8 fp16 values of the ReLU
-    // source / residual operand at the same place (zero when there is none)
-    auto emit = [&](int i, int ps, u32x4 araw) {
-        const int r = ps * RPP + lr;
-        const int m = m0 + wm * WM + i * 32 + r;
-        const int n = n_lane;
-        if (EDGE && (m >= g.M || n >= g.N)) return;
-        const f32x4 s0 = *reinterpret_cast<const f32x4*>(slab + r * SLD + lc);
-        const f32x4 s1 = *reinterpret_cast<const f32x4*>(slab + r * SLD + lc + 4);
-        float       v[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
-        const bool  full = !EDGE || n + 8 <= g.N;
-        const long long mn = (long long)m * g.N + n;
-        if (C32) {  // raw accumulator out: split-K partial, or fp32 result with alpha and addend
+    // (N is a multiple of 8 on this path, so a 16-byte piece of a row is either fully inside or fully outside)
+    if (C32) {  // raw accumulator out: split-K partial, or fp32 result with alpha and addend
+        static_for<TM * TN * 4>([&](auto tc) {
+            constexpr int t = decltype(tc)::value, i = t / (TN * 4), j = (t / 4) % TN, q = t % 4;
+            const int m = mrow + 32 * i, n = ncol + 32 * j + 8 * q + 4 * eh;
+            if (EDGE && (m >= g.M || n >= g.N)) return;
+            f32x4 v = {acc_get(acc[i][j][4 * q]), acc_get(acc[i][j][4 * q + 1]), acc_get(acc[i][j][4 * q + 2]), acc_get(acc[i][j][4 * q + 3])};
+            const long long mn = (long long)m * g.N + n;
             if (!split) {
+                v *= g.alpha;
+                if (g.acc_in) v += *reinterpret_cast<const f32x4*>(g.acc_in + mn);
+            }
+            *reinterpret_cast<f32x4*>(C32 + mn) = v;
+        });
+    } else {
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        typedef float    f32x2 __attribute__((ext_vector_type(2)));
+        typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+        // the uncommon terms first, in fp32: scale factor, fp32 addend, a bias that could not start the accumulators
+        if (g.alpha != 1.f || g.acc_in || (g.bias && !fold_bias)) {
+            static_for<TM * TN * 4>([&](auto tc) {
+                constexpr int t = decltype(tc)::value, i = t / (TN * 4), j = (t / 4) % TN, q = t % 4;
+                const int m = mrow + 32 * i, n = ncol + 32 * j + 8 * q + 4 * eh;
+                const bool in = !EDGE || (m < g.M && n < g.N);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] *= g.alpha;
-                if (g.acc_in) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (full || n + e < g.N) v[e] += g.acc_in[mn + e];
+                for (int e = 0; e < 4; ++e) {
+                    float x = acc_get(acc[i][j][4 * q + e]) * g.alpha;
+                    if (g.acc_in && in) x += g.acc_in[(long long)m * g.N + n + e];
+                    if (g.bias && !fold_bias && in) x += h2f(g.bias[n + e]);
+                    acc[i][j][4 * q + e] = acc_put(x);
                 }
-            }
-            if (full) {
-                *reinterpret_cast<float4*>(C32 + mn)     = make_float4(v[0], v[1], v[2], v[3]);
-                *reinterpret_cast<float4*>(C32 + mn + 4) = make_float4(v[4], v[5], v[6], v[7]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (n + e < g.N) C32[mn + e] = v[e];
-            }
-            return;
+            });
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] *= g.alpha;
-        if (g.acc_in) {
-            if (full) {
-                const float4 t0 = *reinterpret_cast<const float4*>(g.acc_in + mn);
-                const float4 t1 = *reinterpret_cast<const float4*>(g.acc_in + mn + 4);
-                v[0] += t0.x; v[1] += t0.y; v[2] += t0.z; v[3] += t0.w;
-                v[4] += t1.x; v[5] += t1.y; v[6] += t1.z; v[7] += t1.w;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (n + e < g.N) v[e] += g.acc_in[mn + e];
+        constexpr int NCH = TN * 2;  // 16-byte pieces per lane and 32-row block: tile j, piece c -> columns 32 j + 16 c + 8 eh ...
+        u16x2         mag = {0, 0};  // running maximum of the magnitude bits of everything stored (non-finite: >= 0x7C00)
+        // residual / ReLU-source pieces of block i; those of block i + 1 are requested before block i is worked on
+        u32x4 av[2][NCH];
+        auto  aux_load = [&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            static_for<NCH>([&](auto cc) {
+                constexpr int ch = decltype(cc)::value;
+                const int     m = mrow + 32 * i, n = ncol + 16 * ch + 8 * eh;
+                av[i & 1][ch]   = u32x4{0u, 0u, 0u, 0u};
+                if (!EDGE || (m < g.M && n < g.N)) av[i & 1][ch] = *reinterpret_cast<const u32x4*>(aux + (long long)m * g.ld_aux + n);
+            });
+        };
+        if (aux) aux_load(std::integral_constant<int, 0>{});
+        static_for<TM>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            if constexpr (i + 1 < TM) {
+                if (aux) aux_load(std::integral_constant<int, i + 1>{});
             }
-        }
+            __builtin_amdgcn_sched_barrier(0);
+            const int m = mrow + 32 * i;
+            static_for<TN>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                float         v[16];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += bias8[e];
-        if (g.relu) {
+                for (int e = 0; e < 16; ++e) v[e] = acc_get(acc[i][j][e]);
+                if (g.relu) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
-        }
-        uint16_t h[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = f2h(v[e]);
-        if (aux) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float t = h2f((uint16_t)((e & 1) ? (araw[e >> 1] >> 16) : (araw[e >> 1] & 0xFFFFu)));
-                if (g.relu_src) {
-                    if (!(t > 0.f)) h[e] = 0;
-                } else {
-                    h[e] = f2h(h2f(h[e]) + t);
+                    for (int e = 0; e < 16; ++e) v[e] = __builtin_amdgcn_fmed3f(v[e], 0.f, __builtin_inff());  // max(v, 0), NaN -> 0
                 }
-            }
-        }
-        if (g.found_inf) {
+                // one rounding to fp16, packed in pairs: d[2 q], d[2 q + 1] = columns 8 q + 4 eh + {0, 1}, {2, 3}
+                unsigned d[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) bad |= (full || n + e < g.N) && half_nonfinite(h[e]);
-        }
-        uint16_t* dst = C + (long long)m * g.ldc + n;
-        if (full) {
-            *reinterpret_cast<u32x4*>(dst) = u32x4{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
-                                                   (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16)};
-        } else {
+                for (int e = 0; e < 8; ++e) {
+                    const f16x2 hpair = __builtin_convertvector(f32x2{v[2 * e], v[2 * e + 1]}, f16x2);
+                    d[e]              = __builtin_bit_cast(unsigned, hpair);
+                }
+                // lanes er (eh = 0) and er + 32 (eh = 1) trade: afterwards d[4 c .. 4 c + 3] hold, in order, the 8
+                // consecutive columns 16 c + 8 eh ... of row er
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (n + e < g.N) dst[e] = h[e];
-        }
-    };
-
-    // Slabs are private to a wave and LDS operations of one wave execute in order, so no workgroup barrier is
-    // needed between writing a slab and reading it back (the main loop ended with one).
-    static_for<TM>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        u32x4 av[NP];
-        if constexpr (!EDGE) {
-            // all residual / ReLU-source loads of this slab are issued before the LDS round trip
+                for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int ps = 0; ps < NP; ++ps) {
-                av[ps] = u32x4{0u, 0u, 0u, 0u};
-                if (aux) av[ps] = *reinterpret_cast<const u32x4*>(aux + (long long)(m0 + wm * WM + i * 32 + ps * RPP + lr) * g.ld_aux + n_lane);
-            }
-        }
+                    for (int w = 0; w < 2; ++w) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(d[4 * c + w], d[4 * c + 2 + w], false, false);
+                        d[4 * c + w]     = sw[0];
+                        d[4 * c + 2 + w] = sw[1];
+                    }
+                static_for<2>([&](auto cc) {
+                    constexpr int c = decltype(cc)::value;
+                    const int     n = ncol + 32 * j + 16 * c + 8 * eh;
+                    if (EDGE && (m >= g.M || n >= g.N)) return;
+                    u32x4 out = {d[4 * c], d[4 * c + 1], d[4 * c + 2], d[4 * c + 3]};
+                    if (aux) {
+                        const u32x4 a = av[i & 1][2 * j + c];
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+                        for (int w = 0; w < 4; ++w) {
+                            const unsigned ow = out[w], aw = a[w];  // (bit_cast wants whole objects, not vector elements)
+                            const f16x2    hv = __builtin_bit_cast(f16x2, ow), tv = __builtin_bit_cast(f16x2, aw);
+                            f16x2       rv;
+                            if (g.relu_src) {
+                                rv[0] = (tv[0] > (_Float16)0) ? hv[0] : (_Float16)0;
+                                rv[1] = (tv[1] > (_Float16)0) ? hv[1] : (_Float16)0;
+                            } else {
+                                rv = __builtin_convertvector(__builtin_convertvector(hv, f32x2) + __builtin_convertvector(tv, f32x2), f16x2);
+                            }
+                            out[w] = __builtin_bit_cast(unsigned, rv);
+                        }
+                    }
+                    if (g.found_inf) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 v = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-                *reinterpret_cast<f32x4*>(slab + (lane & 31) * SLD + j * 32 + q * 8 + (lane >> 5) * 4) = v;
-            }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        if constexpr (!EDGE) {
-#pragma unroll
-            for (int ps = 0; ps < NP; ++ps) emit(i, ps, av[ps]);
-        } else {
-#pragma unroll 1
-            for (int ps = 0; ps < NP; ++ps) {
-                u32x4     araw = u32x4{0u, 0u, 0u, 0u};
-                const int m    = m0 + wm * WM + i * 32 + ps * RPP + lr;
-                if (aux && m < g.M && n_lane < g.N) araw = load8_guard(aux + (long long)m * g.ld_aux + n_lane, g.N - n_lane);
-                emit(i, ps, araw);
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    });
-    __syncthreads();  // every wave is done with its slab before the next tile's loads overwrite the LDS stages
+                        for (int w = 0; w < 4; ++w) {
+                            const unsigned mw = out[w] & 0x7FFF7FFFu;
+                            mag               = __builtin_elementwise_max(mag, __builtin_bit_cast(u16x2, mw));
+                        }
+                    }
+                    *reinterpret_cast<u32x4*>(C + (long long)m * g.ldc + n) = out;
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        bad |= mag[0] >= 0x7C00 || mag[1] >= 0x7C00;
+    }
     }  // tile loop
     if (g.found_inf && __any(bad)) {
         if (lane == 0) atomicOr(g.found_inf, 1);
@@ -661,7 +677,8 @@ static bool fast_path_ok(const GemmArgs& g) {
     if (!m8(g.sa_o) || !m8(g.sa_i) || !m8(g.sb_o) || !m8(g.sb_i) || !m8(g.sc_o) || !m8(g.sc_i)) return false;
     if ((g.relu_src || g.add) && (!m8(g.ld_aux) || !aligned16(g.relu_src) || !aligned16(g.add))) return false;
     if (g.bias && !aligned16(g.bias)) return false;
-    if ((g.acc_in || g.C32) && ((g.N & 3) != 0 || !aligned16(g.acc_in) || !aligned16(g.C32))) return false;
+    if ((g.N & 7) != 0) return false;  // the epilogue moves 8 columns at a time
+    if ((g.acc_in || g.C32) && (!aligned16(g.acc_in) || !aligned16(g.C32))) return false;
     return true;
 }
 
