@@ -210,6 +210,15 @@ def main():
     t_upd = _time_calls(torch, lambda: B.mp_unscale_check_update(step.P.flat_list, 1, step.cfg, step.st, 1), 10)
     t_upd_chk = _time_calls(torch, lambda: B.mp_unscale_check_update(step.P.flat_list, 1, step.cfg, step.st, 0), 10)
 
+    # what the matrix cores sustain on this device with register-resident operands: all-zero operands (top clock)
+    # and operands distributed like the step's tensors (the clock the chip holds under load depends on the data)
+    probe_sink = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(1805)
+    mfma_rate = {}
+    for name, ops in (("zero_operands", torch.zeros(16384, dtype=torch.float16, device="cuda")),
+                      ("normal_operands", torch.randn(16384, device="cuda", generator=gen).half())):
+        mfma_rate[name] = max(B.mp_mfma_sustained_rate(ops, probe_sink, 512, 60000) for _ in range(2))
+
     # one plain device copy of known size (256 MiB read + 256 MiB write): the calibration launch for the
     # FETCH_SIZE / WRITE_SIZE counters when this script runs under rocprofv3 --pmc
     cal_src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
@@ -239,7 +248,9 @@ def main():
                      "avg_launch_us": secs / n_launch * 1e6, "avg_bracket_us": raw_secs / n_launch * 1e6,
                      "avg_empty_bracket_us": empty_secs / n_launch * 1e6, "flops_per_launch": flops / n_launch,
                      "algorithmic_bytes_per_launch": gemm_bytes / n_launch,
-                     "isolated": {"achieved": iso_flops / iso_secs * 1e-12, "per_call": per}},
+                     "isolated": {"achieved": iso_flops / iso_secs * 1e-12, "per_call": per},
+                     "sustained_mfma_tflops": mfma_rate,
+                     "frac_of_sustained_normal_operands": flops / secs * 1e-12 / mfma_rate["normal_operands"]},
         "roofline_update": {"bound": "hbm", "kernel": "update_kernel<ADAM> (unscale + Adam + fp16 re-cast)",
                             "achieved": upd_bytes / t_upd * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                             "frac": upd_bytes / t_upd * 1e-9 / PEAK_HBM_GBS, "traffic": UPDATE_TRAFFIC_BYTES_PER_LAUNCH,

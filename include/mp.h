@@ -262,6 +262,18 @@ int mp_cast_f32_to_f16(size_t n, const float* src, mp_half* dst, mp_stream strea
 /* Fill n 32-bit words (a kernel, safe inside HIP graph capture). */
 int mp_fill_u32(size_t n, uint32_t value, void* dst, mp_stream stream);
 
+/* Measurement support for the half-precision matrix-unit rate that Section 3 builds on: the rate the matrix
+ * cores sustain on THIS device with operands held in registers, for the operand values the caller supplies.
+ * `workgroups` workgroups of 4 waves each run `iters` iterations of 16 independent 32x32x16 fp16 multiply-
+ * accumulates (fp32 accumulators) and nothing else.  operands: device, >= 16384 halves, 16-byte aligned (the 8
+ * operand registers of every lane; zeros, or values distributed like the tensors of interest: the clock the chip
+ * holds under this load depends on them).  sink: device, >= workgroups * 256 floats, receives the accumulator
+ * sums.  tflops: host, receives 2 * 32 * 32 * 16 flops per instruction over the time between two events on
+ * `stream`.  Blocks until the timed launch has finished.  Errors: MP_E_INVALID for NULL / short / misaligned
+ * buffers or counts out of range. */
+int mp_mfma_sustained_rate(const mp_half* operands, size_t n_operands, float* sink, size_t n_sink, int workgroups,
+                           int iters, double* tflops, mp_stream stream);
+
 /* ------------------------------------------------------------------------------------------
  * Optimizer wrapper (Section 3.2) with the gradient inspection of Section 3.1 and the fp32-side
  * regulariser of Section 3.3.

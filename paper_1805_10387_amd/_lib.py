@@ -72,6 +72,7 @@ SIGNATURES = {
     "mp_lstm_cell_bwd": (_I, [_I, _I, _P, _I, _P, _P, _P, _I, _P, _I, _P, _P, _P]),
     "mp_cast_f32_to_f16": (_I, [_SZ, _P, _P, _P]),
     "mp_fill_u32": (_I, [_SZ, C.c_uint32, _P, _P]),
+    "mp_mfma_sustained_rate": (_I, [_P, _SZ, _P, _SZ, _I, _I, C.POINTER(C.c_double), _P]),
     "mp_unscale_check_update": (_I, [C.POINTER(TensorDesc), _I, C.POINTER(OptCfg), _P, _I, _P]),
 }
 

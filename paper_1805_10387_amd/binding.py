@@ -166,6 +166,14 @@ def mp_fill_u32(n, value, dst):
     _check(L.load().mp_fill_u32(n, value, _p(dst), _stream()))
 
 
+def mp_mfma_sustained_rate(operands, sink, workgroups: int, iters: int) -> float:
+    """TFLOP/s the matrix cores sustain with the given operand values held in registers (blocks)."""
+    out = C.c_double(0.0)
+    _check(L.load().mp_mfma_sustained_rate(_p(operands), operands.numel(), _p(sink), sink.numel(), workgroups, iters,
+                                           C.byref(out), _stream()))
+    return out.value
+
+
 # ------------------------------------------------------------------ optimizer wrapper
 def opt_cfg(kind: str, lr: float, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0) -> OptCfg:
     c = OptCfg()

@@ -177,7 +177,9 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_fwd_kernel(int rows, int
 // column sums of dy*xhat and dy for its rows in registers; they are combined per workgroup in LDS
 // and written as partials part[block][NS][d] (NS = 3 with ZSUM: also the column sums of the stored dz,
 // which is the bias gradient of the linear layer whose output fed this LayerNorm).
-template <bool ZSUM>
+// MAXV = 16-byte vectors per lane (d <= 64 * 8 * MAXV).  The raw vectors of the wave's next row are requested
+// before the current row is reduced, so the two cross-lane reductions of a row overlap the next row's loads.
+template <bool ZSUM, int MAXV>
 __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int d, const uint16_t* __restrict__ dy,
                                                                    const uint16_t* __restrict__ x,
                                                                    const uint16_t* __restrict__ a,
@@ -189,9 +191,9 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int
     constexpr int NS = ZSUM ? 3 : 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nvec = d >> 3;
-    float     gam[LN_MAXV][8], sg[LN_MAXV][8], sb[LN_MAXV][8], sz[ZSUM ? LN_MAXV : 1][8];
+    float     gam[MAXV][8], sg[MAXV][8], sb[MAXV][8], sz[ZSUM ? MAXV : 1][8];
 #pragma unroll
-    for (int i = 0; i < LN_MAXV; ++i) {
+    for (int i = 0; i < MAXV; ++i) {
         const int v = i * 64 + lane;
 #pragma unroll
         for (int k = 0; k < 8; ++k) sg[i][k] = sb[i][k] = gam[i][k] = 0.f;
@@ -201,21 +203,43 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int
         }
         if (v < nvec) unpack8(*reinterpret_cast<const uint4*>(gamma + v * 8), gam[i]);
     }
-    for (int row = blockIdx.x * GL_WAVES + wave; row < rows; row += gridDim.x * GL_WAVES) {
+    const int stride = gridDim.x * GL_WAVES;
+    uint4     rdy[MAXV], rx[MAXV], ra[MAXV];  // raw vectors of the row being worked on
+    float     mean = 0.f, rstd = 0.f;
+    auto fetch = [&](int row, uint4* qdy, uint4* qx, uint4* qa, float& mu, float& rs) {
         const long long base = (long long)row * d;
-        const float     mean = mean_i[row], rstd = rstd_i[row];
-        float           xh[LN_MAXV][8], g[LN_MAXV][8];
+#pragma unroll
+        for (int i = 0; i < MAXV; ++i) {
+            const int v = i * 64 + lane;
+            qdy[i] = qx[i] = qa[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (v < nvec) {
+                qdy[i] = *reinterpret_cast<const uint4*>(dy + base + v * 8);
+                qx[i]  = *reinterpret_cast<const uint4*>(x + base + v * 8);
+                if (a != nullptr) qa[i] = *reinterpret_cast<const uint4*>(a + base + v * 8);
+            }
+        }
+        mu = mean_i[row];
+        rs = rstd_i[row];
+    };
+    int row = blockIdx.x * GL_WAVES + wave;
+    if (row < rows) fetch(row, rdy, rx, ra, mean, rstd);
+    for (; row < rows; row += stride) {
+        uint4 ndy[MAXV], nx[MAXV], na[MAXV];
+        float nmean = 0.f, nrstd = 0.f;
+        if (row + stride < rows) fetch(row + stride, ndy, nx, na, nmean, nrstd);
+        const long long base = (long long)row * d;
+        float           xh[MAXV][8], g[MAXV][8];
         float           s1 = 0.f, s2 = 0.f;
 #pragma unroll
-        for (int i = 0; i < LN_MAXV; ++i) {
+        for (int i = 0; i < MAXV; ++i) {
             const int v = i * 64 + lane;
             if (v < nvec) {
                 float dyv[8];
-                unpack8(*reinterpret_cast<const uint4*>(dy + base + v * 8), dyv);
-                unpack8(*reinterpret_cast<const uint4*>(x + base + v * 8), xh[i]);
+                unpack8(rdy[i], dyv);
+                unpack8(rx[i], xh[i]);
                 if (a != nullptr) {
                     float t[8];
-                    unpack8(*reinterpret_cast<const uint4*>(a + base + v * 8), t);
+                    unpack8(ra[i], t);
 #pragma unroll
                     for (int k = 0; k < 8; ++k) xh[i][k] += t[k];
                 }
@@ -233,7 +257,7 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int
         const float m1 = wave_sum(s1) / (float)d;
         const float m2 = wave_sum(s2) / (float)d;
 #pragma unroll
-        for (int i = 0; i < LN_MAXV; ++i) {
+        for (int i = 0; i < MAXV; ++i) {
             const int v = i * 64 + lane;
             if (v < nvec) {
                 float o[8];
@@ -246,9 +270,17 @@ __global__ __launch_bounds__(GL_THREADS) void layernorm_bwd_kernel(int rows, int
                 }
             }
         }
+#pragma unroll
+        for (int i = 0; i < MAXV; ++i) {
+            rdy[i] = ndy[i];
+            rx[i]  = nx[i];
+            ra[i]  = na[i];
+        }
+        mean = nmean;
+        rstd = nrstd;
     }
 #pragma unroll
-    for (int i = 0; i < LN_MAXV; ++i) {
+    for (int i = 0; i < MAXV; ++i) {
         const int v = i * 64 + lane;
         if (v < nvec) {
 #pragma unroll
@@ -566,12 +598,22 @@ extern "C" int mp_layernorm_bwd(int rows, int d, const mp_half* dy, const mp_hal
     float*      part = static_cast<float*>(ws);
     hipStream_t hs   = as_stream(stream);
     const size_t lds = (size_t)GL_WAVES * ns * d * sizeof(float);
-    if (dz_colsum)
-        hipLaunchKernelGGL(layernorm_bwd_kernel<true>, dim3(nb), dim3(GL_THREADS), lds, hs, rows, d, dy, x, a, gamma, mean,
-                           rstd, dz, part);
-    else
-        hipLaunchKernelGGL(layernorm_bwd_kernel<false>, dim3(nb), dim3(GL_THREADS), lds, hs, rows, d, dy, x, a, gamma, mean,
-                           rstd, dz, part);
+    const bool small = d <= 64 * 8 * 2;  // two vectors per lane are enough: fewer registers, more waves per CU
+    if (dz_colsum) {
+        if (small)
+            hipLaunchKernelGGL((layernorm_bwd_kernel<true, 2>), dim3(nb), dim3(GL_THREADS), lds, hs, rows, d, dy, x, a, gamma,
+                               mean, rstd, dz, part);
+        else
+            hipLaunchKernelGGL((layernorm_bwd_kernel<true, LN_MAXV>), dim3(nb), dim3(GL_THREADS), lds, hs, rows, d, dy, x, a,
+                               gamma, mean, rstd, dz, part);
+    } else {
+        if (small)
+            hipLaunchKernelGGL((layernorm_bwd_kernel<false, 2>), dim3(nb), dim3(GL_THREADS), lds, hs, rows, d, dy, x, a, gamma,
+                               mean, rstd, dz, part);
+        else
+            hipLaunchKernelGGL((layernorm_bwd_kernel<false, LN_MAXV>), dim3(nb), dim3(GL_THREADS), lds, hs, rows, d, dy, x, a,
+                               gamma, mean, rstd, dz, part);
+    }
     MP_LAUNCH_CHECK("mp_layernorm_bwd");
     FinishOuts outs{{dgamma, dbeta, dz_colsum}};
     hipLaunchKernelGGL(finish_colsum_kernel, dim3((ns * d + 31) / 32), dim3(GL_THREADS), 0, hs, part, nb, (long long)ns * d,
