@@ -48,8 +48,8 @@ def _time_calls(torch, fn, reps):
 
 
 def gemm_roofline(torch, B, step, reps=20):
-    """Time each distinct dense contraction of one layer in isolation (same descriptors, same buffers as
-    the step uses) and aggregate: algorithmic flops = 2 M N K per launch."""
+    """Time each distinct dense-contraction launch of one layer in isolation (same descriptors, same buffers as
+    the step uses) and aggregate: algorithmic flops = 2 M N K per product."""
     wl, w, g, a = step.wl, step.P.w16, step.P.g16, step.act[0]
     tb = step.tmp[0]
     dqkv, dz1, dz2, df = tb["dqkv"], tb["dz1"], tb["dz2"], tb["df"]
@@ -64,11 +64,18 @@ def gemm_roofline(torch, B, step, reps=20):
         "dx_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dx(step.d_o, dz1, w["l0.wo"], step.dctx)),
         "dx_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f1, df, w["l0.w1"], step.dy1, add=dz2, ld_aux=d)),
         "dx_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f2, dz2, w["l0.w2"], df, relu_src=a["f"], ld_aux=f)),
-        "dw_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dw(step.d_qkv, dqkv, x, g["l0.wqkv"], None, st, ws)),
-        "dw_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dw(step.d_o, dz1, a["ctx"], g["l0.wo"], None, st, ws)),
-        "dw_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f1, df, a["y1"], g["l0.w1"], None, st, ws)),
-        "dw_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f2, dz2, a["f"], g["l0.w2"], None, st, ws)),
     }
+    if step.grouped_dw:
+        grp = B.gemm_group([(step.d_f2, dz2, a["f"], g["l0.w2"]), (step.d_f1, df, a["y1"], g["l0.w1"]),
+                            (step.d_qkv, dqkv, x, g["l0.wqkv"]), (step.d_o, dz1, a["ctx"], g["l0.wo"])])
+        calls["dw_grouped(qkv,o,ffn1,ffn2)"] = (2.0 * T * (4 * d * d + 2 * f * d), lambda: B.mp_gemm_bwd_dw_grouped(grp, st))
+    else:
+        calls.update({
+            "dw_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dw(step.d_qkv, dqkv, x, g["l0.wqkv"], None, st, ws)),
+            "dw_o": (2.0 * T * d * d, lambda: B.mp_gemm_bwd_dw(step.d_o, dz1, a["ctx"], g["l0.wo"], None, st, ws)),
+            "dw_ffn1": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f1, df, a["y1"], g["l0.w1"], None, st, ws)),
+            "dw_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dw(step.d_f2, dz2, a["f"], g["l0.w2"], None, st, ws)),
+        })
     per, flops, secs = {}, 0.0, 0.0
     for name, (fl, fn) in calls.items():
         t = _time_calls(torch, fn, reps)
@@ -83,7 +90,7 @@ class GemmTimer:
     with a pair of events on the launch stream while the step runs eagerly, so each launch is timed where it
     runs in the step: same operands, same cache state, same neighbours.  flops = 2 M N K x batches."""
 
-    NAMES = ("mp_gemm_fwd", "mp_gemm_bwd_dx", "mp_gemm_bwd_dw")
+    NAMES = ("mp_gemm_fwd", "mp_gemm_bwd_dx", "mp_gemm_bwd_dw", "mp_gemm_bwd_dw_grouped")
 
     def __init__(self, torch, B):
         self.torch, self.B, self.saved, self.rec = torch, B, {}, []
@@ -93,13 +100,15 @@ class GemmTimer:
             fn = getattr(self.B, name)
             self.saved[name] = fn
 
-            def timed(desc, *a, _fn=fn, **kw):
+            def timed(desc, *a, _fn=fn, _name=name, **kw):
                 e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
                 e0.record()
                 r = _fn(desc, *a, **kw)
                 e1.record()
-                fl = 2.0 * desc.M * desc.N * desc.K * max(desc.batch_outer, 1) * max(desc.batch_inner, 1)
-                byts = 2.0 * (desc.M * desc.K + desc.K * desc.N + desc.M * desc.N) * max(desc.batch_outer, 1) * max(desc.batch_inner, 1)
+                # (the grouped entry point takes an array of items, each with its own descriptor)
+                descs = [it.desc for it in desc] if _name == "mp_gemm_bwd_dw_grouped" else [desc]
+                fl = sum(2.0 * q.M * q.N * q.K * max(q.batch_outer, 1) * max(q.batch_inner, 1) for q in descs)
+                byts = sum(2.0 * (q.M * q.K + q.K * q.N + q.M * q.N) * max(q.batch_outer, 1) * max(q.batch_inner, 1) for q in descs)
                 # an empty bracket right behind it: what two event records cost on this stream with nothing between
                 z0, z1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
                 z0.record()
@@ -240,7 +249,7 @@ def main():
         "step_gemm_tflops": wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12,
         "step_mfma_util_pct": 100.0 * wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12 / PEAK_FP16_TFLOPS,
         "final_loss": loss, "loss_scale": st.scale, "opt_steps": st.opt_step, "skipped": st.skipped_steps,
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (every dense fp16 contraction of the step: per layer 4 fwd, 4 dX, 4 dW)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel / gemm_grouped_kernel (every dense fp16 contraction of the step: per layer 4 fwd, 4 dX, and the 4 dW in one grouped launch)",
                      "achieved": flops / secs * 1e-12, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / secs * 1e-12 / PEAK_FP16_TFLOPS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,

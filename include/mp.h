@@ -161,6 +161,22 @@ int mp_gemm_bwd_dw(const mp_gemm_desc* desc /* host */, const mp_half* dY, const
                    mp_half* dW, mp_half* db, mp_scale_state* st, void* ws, size_t ws_bytes,
                    mp_stream stream);
 
+/* Several weight-gradient products (Section 3.1: fp16 operands, fp32 accumulation, one rounding) in one launch.
+ * Each of a layer's dW = dY^T X alone has too few output tiles to occupy the chip without splitting its
+ * contraction; together they do.  items: host array of `count` (1..8) problems, each a descriptor as for
+ * mp_gemm_bwd_dw (same meaning of M, N, K, ldx, ldw, ldy, trans_w, alpha; no batches) with its device pointers.
+ * The overflow flag of `st` (may be NULL) is set if any stored gradient is non-finite.  No bias gradients here
+ * (mp_colsum).  MP_E_UNSUPPORTED, with nothing launched, if an item is batched, fails the 16-byte / multiple-of-8
+ * alignment rules of the fast path, or has a weight shape that is not a multiple of 128 in both dimensions or a
+ * row count (M) that is not a multiple of 64: use mp_gemm_bwd_dw for those. */
+typedef struct mp_gemm_group_item {
+    mp_gemm_desc   desc;
+    const mp_half* dY;
+    const mp_half* X;
+    mp_half*       dW;
+} mp_gemm_group_item;
+int mp_gemm_bwd_dw_grouped(const mp_gemm_group_item* items, int count, mp_scale_state* st, mp_stream stream);
+
 /* Tuning aid, process-wide and not thread-safe: force every following contraction onto tile shape `tile`
  * (index into the library's tile table: 0 = 256x256, 1 = 256x128, 2 = 128x256, 3 = 128x128, 4 = 128x64,
  * 5 = 64x128, 6 = 64x64, 7 = 32x128) and, where splitting the contraction is allowed, onto `splits` splits.

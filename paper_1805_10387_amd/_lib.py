@@ -33,6 +33,10 @@ class GemmDesc(C.Structure):
                 ("alpha", C.c_float), ("epilogue", C.c_int32), ("trans_w", C.c_int32), ("reserved", C.c_int32)]
 
 
+class GemmGroupItem(C.Structure):
+    _fields_ = [("desc", GemmDesc), ("dY", C.c_void_p), ("X", C.c_void_p), ("dW", C.c_void_p)]
+
+
 class TensorDesc(C.Structure):
     _fields_ = [("g16", C.c_void_p), ("w32", C.c_void_p), ("w16", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("n", C.c_size_t)]
@@ -55,6 +59,7 @@ SIGNATURES = {
     "mp_gemm_fwd": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, _P, _P, _P]),
     "mp_gemm_bwd_dx": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, C.c_int32, _P, _P]),
     "mp_gemm_bwd_dw": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mp_gemm_bwd_dw_grouped": (_I, [C.POINTER(GemmGroupItem), _I, _P, _P]),
     "mp_gemm_tuning_override": (_I, [_I, _I]),
     "mp_colsum_workspace_bytes": (_SZ, [_I, _I]),
     "mp_colsum": (_I, [_I, _I, _P, _I, _P, _P, _P, _SZ, _P]),

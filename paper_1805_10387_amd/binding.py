@@ -90,6 +90,20 @@ def mp_gemm_bwd_dw(desc: GemmDesc, dY, X, dW, db=None, st=None, ws=None):
                                    0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 
+def gemm_group(items):
+    """Host array for mp_gemm_bwd_dw_grouped from (desc, dY, X, dW) tuples; keeps the tensors alive."""
+    arr = (L.GemmGroupItem * len(items))()
+    for k, (desc, dY, X, dW) in enumerate(items):
+        C.memmove(C.byref(arr[k].desc), C.byref(desc), C.sizeof(GemmDesc))
+        arr[k].dY, arr[k].X, arr[k].dW = _p(dY), _p(X), _p(dW)
+    arr._keep = [t for it in items for t in it[1:]]
+    return arr
+
+
+def mp_gemm_bwd_dw_grouped(group, st=None):
+    _check(L.load().mp_gemm_bwd_dw_grouped(group, len(group), _p(st), _stream()))
+
+
 def mp_gemm_tuning_override(tile: int, splits: int = 1):
     _check(L.load().mp_gemm_tuning_override(tile, splits))
 

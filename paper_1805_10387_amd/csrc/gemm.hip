@@ -203,38 +203,28 @@ struct LoaderSel<R, false> { typedef OCLoader<R> T; };
 
 // EDGE = false: every tile lies fully inside the matrices and K is a multiple of BK, so neither the
 // loads nor the stores carry bounds tests.  EDGE = true: every access is tested (ragged shapes).
+// One output tile: tile number `pid` of problem g (tiles are numbered in bands of GROUP tile-rows), batch `by`, k-split
+// `bz` of `nz`.  EDGE = false: every tile lies fully inside the matrices and K is a multiple of BK, so neither the
+// loads nor the stores carry bounds tests.  EDGE = true: every access is tested (ragged shapes).
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool EDGE>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, const int by, const int bz, const int nz, char* smem,
+                                          bool& bad) {
     static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 matrix-core tiles per wave
     static_assert(TM >= 1 && TN >= 1, "wave tile at least 32x32");
     constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
 
-    extern __shared__ __align__(16) char smem[];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int bo = blockIdx.y / g.batch_inner, bi = blockIdx.y - bo * g.batch_inner;
+    const int bo = by / g.batch_inner, bi = by - bo * g.batch_inner;
     const uint16_t* A = g.A + bo * g.sa_o + bi * g.sa_i;
     const uint16_t* B = g.B + bo * g.sb_o + bi * g.sb_i;
-    const int kbeg = blockIdx.z * g.k_per_split;
+    const int kbeg = bz * g.k_per_split;
     const int kend = min(g.K, kbeg + g.k_per_split);
     const int nkt  = (kend - kbeg + BK - 1) / BK;
-    bool      bad  = false;
 
-    // ---- persistent over tiles: workgroup w takes tiles w, w + gridDim.x, ...  The stores of one tile's
-    // epilogue drain while the next tile's first loads are in flight.
-    const int ntiles = g.tiles_m * g.tiles_n;
-    for (int vb = blockIdx.x; vb < ntiles; vb += gridDim.x) {
-    // which tile: consecutive ids are dispatched round-robin over the 8 XCDs (gridDim.x is a multiple of 8
-    // whenever a workgroup takes more than one tile), so id -> (id % 8) * (ntiles / 8) + id / 8 gives each XCD
-    // a contiguous run of tiles; tiles are then walked in bands of GROUP tile-rows.
-    int pid = vb;
-    {
-        const int q = ntiles >> 3, rem = ntiles & 7, x = pid & 7, local = pid >> 3;
-        pid = x * q + min(x, rem) + local;
-    }
     constexpr int GROUP = 4;
     const int     band  = pid / (GROUP * g.tiles_n);
     const int     first = band * GROUP;
@@ -397,8 +387,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
     uint16_t*       C   = g.C ? g.C + bo * g.sc_o + bi * g.sc_i : nullptr;
     const uint16_t* aux = g.relu_src ? g.relu_src : g.add;
     if (aux) aux += bo * g.sc_o + bi * g.sc_i;
-    float*     C32   = g.C32 ? g.C32 + (long long)blockIdx.z * g.M * g.N : nullptr;
-    const bool split = gridDim.z > 1;
+    float*     C32   = g.C32 ? g.C32 + (long long)bz * g.M * g.N : nullptr;
+    const bool split = nz > 1;
     const int  mrow = m0 + wm * WM + er;  // + 32 i
 
     // (N is a multiple of 8 on this path, so a 16-byte piece of a row is either fully inside or fully outside)
@@ -516,9 +506,63 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
         });
         bad |= mag[0] >= 0x7C00 || mag[1] >= 0x7C00;
     }
-    }  // tile loop
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool EDGE>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
+    extern __shared__ __align__(16) char smem[];
+    bool bad = false;
+    // Persistent over tiles: workgroup w takes tiles w, w + gridDim.x, ...  The stores of one tile's epilogue
+    // drain while the next tile's first loads are in flight.
+    const int ntiles = g.tiles_m * g.tiles_n;
+    for (int vb = blockIdx.x; vb < ntiles; vb += gridDim.x) {
+        // consecutive ids are dispatched round-robin over the 8 XCDs (gridDim.x is a multiple of 8 whenever a
+        // workgroup takes more than one tile), so id -> (id % 8) * (ntiles / 8) + id / 8 gives each XCD, and its
+        // L2, a contiguous run of tiles
+        const int q = ntiles >> 3, rem = ntiles & 7, x = vb & 7, local = vb >> 3;
+        const int pid = x * q + min(x, rem) + local;
+        gemm_tile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, EDGE>(g, pid, blockIdx.y, blockIdx.z, gridDim.z, smem, bad);
+    }
     if (g.found_inf && __any(bad)) {
-        if (lane == 0) atomicOr(g.found_inf, 1);
+        if ((threadIdx.x & 63) == 0) atomicOr(g.found_inf, 1);
+    }
+}
+
+// Several independent problems of one operand layout in one launch (the weight-gradient products of a layer: each
+// alone has too few tiles for the chip).  Tiles of all problems are numbered one after the other, largest problem
+// first; no batches, no k-splits.
+constexpr int GROUP_MAX = 8;
+struct GroupArgs {
+    GemmArgs p[GROUP_MAX];
+    int      tile_start[GROUP_MAX + 1];
+    int      count;
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_grouped_kernel(GroupArgs ga) {
+    extern __shared__ __align__(16) char smem[];
+    bool      bad_any = false;
+    int*      flag    = ga.p[0].found_inf;  // one flag for the whole group
+    const int total   = ga.tile_start[ga.count];
+    for (int vb = blockIdx.x; vb < total; vb += gridDim.x) {
+        // the problem this tile belongs to: chosen with wave-uniform selects over statically indexed entries, so
+        // the descriptor stays in scalar registers
+        GemmArgs g     = ga.p[0];
+        int      first = 0;
+#pragma unroll
+        for (int q = 1; q < GROUP_MAX; ++q) {
+            if (q < ga.count && vb >= ga.tile_start[q]) {
+                g     = ga.p[q];
+                first = ga.tile_start[q];
+            }
+        }
+        bool bad = false;
+        gemm_tile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, false>(g, vb - first, 0, 0, 1, smem, bad);
+        bad_any |= bad;
+        __syncthreads();  // (tiles of different problems: keep the LDS stages of one tile apart from the next)
+    }
+    if (flag && __any(bad_any)) {
+        if ((threadIdx.x & 63) == 0) atomicOr(flag, 1);
     }
 }
 
@@ -859,4 +903,74 @@ extern "C" int mp_gemm_bwd_dw(const mp_gemm_desc* d, const mp_half* dY, const mp
         return mp_colsum(d->M, d->N, dY, d->ldy, db, st, cs_ws, cs_b, stream);
     }
     return MP_OK;
+}
+
+template <int BM, int BN>
+static int launch_grouped(const GroupArgs& ga, int resident, hipStream_t hs) {
+    constexpr size_t  lds = 2 * (size_t)(BM + BN) * 128;
+    static std::once_flag once;
+    static hipError_t     attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_grouped_kernel<BM, BN, 2, 2, false, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    if (attr_err != hipSuccess) return hip_fail(attr_err, "gemm: hipFuncSetAttribute(LDS size)");
+    const int total = ga.tile_start[ga.count];
+    hipLaunchKernelGGL((gemm_grouped_kernel<BM, BN, 2, 2, false, false>), dim3(total < resident ? total : resident),
+                       dim3(GEMM_THREADS), lds, hs, ga);
+    MP_LAUNCH_CHECK("grouped gemm launch");
+    return MP_OK;
+}
+
+extern "C" int mp_gemm_bwd_dw_grouped(const mp_gemm_group_item* items, int count, mp_scale_state* st, mp_stream stream) {
+    MP_REQUIRE(items != nullptr && count >= 1 && count <= GROUP_MAX, "mp_gemm_bwd_dw_grouped: 1..%d items", GROUP_MAX);
+    GemmArgs args[GROUP_MAX];
+    bool     all256 = true, all128 = true;
+    for (int i = 0; i < count; ++i) {
+        const mp_gemm_desc* d = &items[i].desc;
+        int rc = check_desc(d, "mp_gemm_bwd_dw_grouped");
+        if (rc) return rc;
+        MP_REQUIRE(items[i].dY && items[i].X && items[i].dW, "mp_gemm_bwd_dw_grouped: item %d has a NULL operand", i);
+        GemmArgs& g = args[i];
+        zero_args(g);
+        g.C = items[i].dW; g.found_inf = st ? &st->found_inf : nullptr;
+        g.K = d->M; g.ldc = d->ldw; g.batch_inner = 1; g.alpha = d->alpha;
+        if (!d->trans_w) {  // dW[N,K] = dY^T X
+            g.A = items[i].dY; g.lda = d->ldy; g.M = d->N;
+            g.B = items[i].X;  g.ldb = d->ldx; g.N = d->K;
+        } else {  // dW[K,N] = X^T dY
+            g.A = items[i].X;  g.lda = d->ldx; g.M = d->K;
+            g.B = items[i].dY; g.ldb = d->ldy; g.N = d->N;
+        }
+        g.k_per_split = g.K;
+        const bool ok = d->batch_outer == 1 && d->batch_inner == 1 && fast_path_ok(g) && g.K > 0 && g.K % BK == 0 &&
+                        g.M % 128 == 0 && g.N % 128 == 0;
+        if (!ok) {
+            set_error("mp_gemm_bwd_dw_grouped: item %d is batched, unaligned, or its shape is not a multiple of 128 "
+                      "(weights) / 64 (rows); use mp_gemm_bwd_dw", i);
+            return MP_E_UNSUPPORTED;
+        }
+        all256 = all256 && g.M % 256 == 0 && g.N % 256 == 0;
+    }
+    (void)all128;
+    const int bm = all256 ? 256 : 128;
+    // longest contraction first, so that the tiles that take longest start first
+    int order[GROUP_MAX];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    for (int i = 1; i < count; ++i)
+        for (int j = i; j > 0 && args[order[j]].K > args[order[j - 1]].K; --j) std::swap(order[j], order[j - 1]);
+    GroupArgs ga{};
+    ga.count = count;
+    long long total = 0;
+    for (int i = 0; i < count; ++i) {
+        GemmArgs g = args[order[i]];
+        g.tiles_m  = g.M / bm;
+        g.tiles_n  = g.N / bm;
+        ga.p[i]          = g;
+        ga.tile_start[i] = (int)total;
+        total += (long long)g.tiles_m * g.tiles_n;
+    }
+    MP_REQUIRE(total < (1 << 24), "mp_gemm_bwd_dw_grouped: too many tiles");
+    for (int i = count; i <= GROUP_MAX; ++i) ga.tile_start[i] = (int)total;
+    return all256 ? launch_grouped<256, 256>(ga, kCUs, as_stream(stream)) : launch_grouped<128, 128>(ga, 2 * kCUs, as_stream(stream));
 }

@@ -153,7 +153,7 @@ class MLPStep(_StepBase):
 class TransformerStep(_StepBase):
     """Stack of post-LayerNorm encoder layers with an MSE loss on the last output (configs 2, 3)."""
 
-    def __init__(self, wl, masters=None, two_streams=False, fused_attention=True, **kw):
+    def __init__(self, wl, masters=None, two_streams=False, fused_attention=True, grouped_dw=True, **kw):
         if masters is None:
             masters = {f"l{i}.{k}": v for i, lay in enumerate(wl.masters()) for k, v in lay.items()}
         super().__init__(masters, wl.opt, wl.scale, **kw)
@@ -164,6 +164,11 @@ class TransformerStep(_StepBase):
         # runs the unfused chain of batched products and softmax kernels
         self.fused_attention = fused_attention and dk_ == 64 and wl.seq_len <= 128 and wl.seq_len % 8 == 0
         self.alpha = 1.0 / math.sqrt(dk_)
+        # one launch for the four weight-gradient products of a layer (each alone has too few tiles for the chip);
+        # needs weight shapes in multiples of 128 and a token count in multiples of 64
+        self.grouped_dw = (grouped_dw and wl.d_model % 128 == 0 and wl.d_ff % 128 == 0
+                           and wl.tokens % 64 == 0)
+        self._groups = {}
         self.side_stream = torch.cuda.Stream() if two_streams else None
         T, d, f, h, S, NB = wl.tokens, wl.d_model, wl.d_ff, wl.n_heads, wl.seq_len, wl.n_seq
         dk = d // h
@@ -259,16 +264,21 @@ class TransformerStep(_StepBase):
                                g[p + "ln2_g"], g[p + "ln2_b"], st, ws, dz_colsum=g[p + "b2"])
             self._t("dy2", l, dy2)
             self._t("dz2", l, dz2)
-            fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f2, dz2, a["f"], g[p + "w2"], None, st, wsx))
+            if not self.grouped_dw:
+                fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f2, dz2, a["f"], g[p + "w2"], None, st, wsx))
             B.mp_gemm_bwd_dx(self.d_f2, dz2, w[p + "w2"], df, relu_src=a["f"], ld_aux=f)
             self._t("df", l, df)
-            fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f1, df, a["y1"], g[p + "w1"], g[p + "b1"], st, wsx))
+            if self.grouped_dw:
+                B.mp_colsum(T, f, df, f, g[p + "b1"], st, ws)
+            else:
+                fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f1, df, a["y1"], g[p + "w1"], g[p + "b1"], st, wsx))
             B.mp_gemm_bwd_dx(self.d_f1, df, w[p + "w1"], self.dy1, add=dz2, ld_aux=d)
             self._t("dy1", l, self.dy1)
             B.mp_layernorm_bwd(T, d, self.dy1, x, a["a"], w[p + "ln1_g"], a["mean1"], a["rstd1"], dz1,
                                g[p + "ln1_g"], g[p + "ln1_b"], st, ws, dz_colsum=g[p + "bo"])
             self._t("dz1", l, dz1)
-            fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_o, dz1, a["ctx"], g[p + "wo"], None, st, wsx))
+            if not self.grouped_dw:
+                fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_o, dz1, a["ctx"], g[p + "wo"], None, st, wsx))
             B.mp_gemm_bwd_dx(self.d_o, dz1, w[p + "wo"], self.dctx)
             self._t("dctx", l, self.dctx)
             # attention: dP = dctx V^T, dV = P^T dctx, dS = softmax', dQ = alpha dS K, dK = alpha dS^T Q
@@ -283,9 +293,19 @@ class TransformerStep(_StepBase):
                 B.mp_gemm_bwd_dx(self.d_s, self.dp, a["qkv"][:, d:], dqkv)
                 B.mp_gemm_bwd_dw(self.d_s, self.dp, a["qkv"], dqkv[:, d:], None, None, ws)
             self._t("dqkv", l, dqkv)
-            fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_qkv, dqkv, x, g[p + "wqkv"], g[p + "bqkv"], st, wsx))
+            if self.grouped_dw:
+                B.mp_colsum(T, 3 * d, dqkv, 3 * d, g[p + "bqkv"], st, ws)
+            else:
+                fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_qkv, dqkv, x, g[p + "wqkv"], g[p + "bqkv"], st, wsx))
             B.mp_gemm_bwd_dx(self.d_qkv, dqkv, w[p + "wqkv"], dx, add=dz1, ld_aux=d)
             self._t("dx", l, dx)
+            if self.grouped_dw:
+                # all four operand pairs of this layer are still in place (the temporaries alternate by layer)
+                key = (l, i % 2)
+                if key not in self._groups:
+                    self._groups[key] = B.gemm_group([(self.d_f2, dz2, a["f"], g[p + "w2"]), (self.d_f1, df, a["y1"], g[p + "w1"]),
+                                                      (self.d_qkv, dqkv, x, g[p + "wqkv"]), (self.d_o, dz1, a["ctx"], g[p + "wo"])])
+                fork(lambda wsx: B.mp_gemm_bwd_dw_grouped(self._groups[key], st))
             if side is not None:
                 done[i] = torch.cuda.Event()
                 done[i].record(side)

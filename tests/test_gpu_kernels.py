@@ -214,6 +214,51 @@ def test_gemm_split_k_weight_gradient():
     assert_close16(db, db_ref, 1e-3, max_ulp=1, what="db")
 
 
+@pytest.mark.parametrize("shapes", [
+    [(192, 256, 128), (192, 128, 384), (192, 384, 256)],      # multiples of 128 only: 128 x 128 tiles
+    [(128, 256, 512), (128, 512, 256), (128, 256, 256)],      # multiples of 256: 256 x 256 tiles
+    [(320, 1024, 256)] * 5,                                     # more tiles than workgroups resident at once
+])
+def test_gemm_grouped_weight_gradients(shapes):
+    """Several dW = dY^T X in one launch: each equals the oracle and, bit for bit, the single-problem entry point."""
+    r = RNG(len(shapes) * 7 + shapes[0][1])
+    items, refs, singles = [], [], []
+    st = make_state()
+    all256 = all(n % 256 == 0 and k % 256 == 0 for (_, n, k) in shapes)
+    for (M, N, K) in shapes:
+        x, dy = S16(r.standard_normal((M, K))), S16(r.standard_normal((M, N)) * 0.1)
+        d = mp.gemm_desc(M, N, K)
+        dw, dw1 = empty16(N, K), empty16(N, K)
+        items.append((d, h16(dy), h16(x), dw))
+        refs.append(L.linear_bwd(MIXED, dy, x, np.zeros((N, K), np.float32))[1])
+        mp.mp_gemm_tuning_override(0 if all256 else 3, 1)         # the tile the grouped launch takes, no k-split
+        mp.mp_gemm_bwd_dw(d, items[-1][1], items[-1][2], dw1, None, None, ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, False)))
+        mp.mp_gemm_tuning_override(-1, 0)
+        singles.append(dw1)
+    mp.mp_gemm_bwd_dw_grouped(mp.gemm_group(items), st)
+    for k, (it, ref, one) in enumerate(zip(items, refs, singles)):
+        assert_close16(it[3], ref, 1e-3, max_ulp=1, what=f"grouped dw {k}")
+        assert torch.equal(it[3], one), f"grouped dw {k} differs from the single-problem result"
+    assert mp.scale_state_read(st).found_inf == 0
+
+
+def test_gemm_grouped_flags_overflow_and_rejects_ragged_shapes():
+    M, N, K = 128, 128, 128
+    big = torch.full((M, N), 300.0, dtype=torch.float16, device="cuda")
+    x = torch.full((M, K), 300.0, dtype=torch.float16, device="cuda")
+    ok_dy, ok_x = torch.ones(M, N, dtype=torch.float16, device="cuda"), torch.ones(M, K, dtype=torch.float16, device="cuda")
+    st = make_state()
+    d = mp.gemm_desc(M, N, K)
+    dw0, dw1 = empty16(N, K), empty16(N, K)
+    mp.mp_gemm_bwd_dw_grouped(mp.gemm_group([(d, ok_dy, ok_x, dw0), (d, big, x, dw1)]), st)
+    assert mp.scale_state_read(st).found_inf == 1          # 128 * 300 * 300 overflows fp16
+    assert torch.all(dw0 == 128.0) and torch.all(torch.isinf(dw1))
+    bad = mp.gemm_desc(128, 136, 128)
+    with pytest.raises(mp.MPError) as e:
+        mp.mp_gemm_bwd_dw_grouped(mp.gemm_group([(bad, empty16(128, 136), ok_x, empty16(136, 128))]), st)
+    assert e.value.code == ML.MP_E_UNSUPPORTED
+
+
 def test_gemm_rejects_bad_arguments():
     d = mp.gemm_desc(8, 8, 8)
     with pytest.raises(mp.MPError) as e:
