@@ -544,7 +544,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_grouped_kernel(GroupArgs ga
     bool      bad_any = false;
     int*      flag    = ga.p[0].found_inf;  // one flag for the whole group
     const int total   = ga.tile_start[ga.count];
-    for (int vb = blockIdx.x; vb < total; vb += gridDim.x) {
+    for (int vb0 = blockIdx.x; vb0 < total; vb0 += gridDim.x) {
+        // consecutive workgroup ids go round-robin over the 8 XCDs: give each XCD, and its L2, a contiguous run of
+        // tiles (neighbouring tiles share operand panels)
+        const int xq = total >> 3, xrem = total & 7, xx = vb0 & 7;
+        const int vb = xx * xq + min(xx, xrem) + (vb0 >> 3);
         // the problem this tile belongs to: chosen with wave-uniform selects over statically indexed entries, so
         // the descriptor stays in scalar registers
         GemmArgs g     = ga.p[0];
