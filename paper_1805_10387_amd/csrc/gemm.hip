@@ -638,7 +638,11 @@ struct TileCfg {
     float eff;  // relative per-flop efficiency of the tile shape (bigger tiles reuse LDS data more)
 };
 static const TileCfg kTiles[] = {{256, 256, 1.00f}, {256, 128, 0.85f}, {128, 256, 0.85f}, {128, 128, 0.65f},
-                                 {128, 64, 0.45f},  {64, 128, 0.45f},  {64, 64, 0.30f},   {32, 128, 0.25f}};
+                                 {128, 64, 0.45f},  {64, 128, 0.45f},  {64, 64, 0.30f},   {32, 128, 0.25f},
+                                 // only when both operands are stored contraction-contiguous (the transposing loader
+                                 // wants a power-of-two tile edge): fills the chip evenly when N is a multiple of 192 only
+                                 {256, 192, 0.78f}};
+constexpr int   kTileKcOnly = 8;  // first index of the shapes restricted to that operand layout
 constexpr int   kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int   kCUs      = 256;
 
@@ -674,6 +678,9 @@ static int launch_tile(int t, const GemmArgs& g, dim3 grid, hipStream_t hs) {
         case 4: return launch_one<128, 64, 2, 2, AKC, BKC>(g, grid, hs);
         case 5: return launch_one<64, 128, 2, 2, AKC, BKC>(g, grid, hs);
         case 6: return launch_one<64, 64, 2, 2, AKC, BKC>(g, grid, hs);
+        case 8:
+            if constexpr (AKC && BKC) return launch_one<256, 192, 2, 2, AKC, BKC>(g, grid, hs);
+            [[fallthrough]];
         default: return launch_one<32, 128, 1, 4, AKC, BKC>(g, grid, hs);
     }
 }
@@ -685,17 +692,17 @@ static int g_force_tile = -1, g_force_splits = 1;
 
 // Pick the tile shape (and split count when allowed) that minimises an estimate of run time:
 // rounds of 256 workgroups x work per workgroup / shape efficiency.
-static Plan make_plan(int M, int N, int K, long long batches, bool allow_split) {
+static Plan make_plan(int M, int N, int K, long long batches, bool allow_split, bool kc_kc = false) {
     // tuning aid (mp_gemm_tuning_override): force a tile shape / split count
     if (g_force_tile >= 0) {
-        int t = g_force_tile < kNumTiles ? g_force_tile : 0, sp = allow_split ? g_force_splits : 1;
+        int t = g_force_tile < (kc_kc ? kNumTiles : kTileKcOnly) ? g_force_tile : 0, sp = allow_split ? g_force_splits : 1;
         if (sp < 1) sp = 1;
         const int kps = ((K + sp - 1) / sp + BK - 1) / BK * BK;
         return Plan{t, sp, kps > 0 ? kps : BK};
     }
     Plan   best{0, 1, 0};
     double best_cost = 1e300;
-    for (int t = 0; t < kNumTiles; ++t) {
+    for (int t = 0; t < (kc_kc ? kNumTiles : kTileKcOnly); ++t) {
         const long long tm = (M + kTiles[t].bm - 1) / kTiles[t].bm, tn = (N + kTiles[t].bn - 1) / kTiles[t].bn;
         const long long tiles = tm * tn * batches;
         const int       max_s = allow_split ? 16 : 1;
@@ -746,8 +753,8 @@ static int run_gemm(GemmArgs g, bool a_kc, bool b_kc, long long batches, bool al
         MP_LAUNCH_CHECK("gemm (generic)");
         return MP_OK;
     }
-    Plan p = make_plan(g.M, g.N, g.K, batches, allow_split && ws != nullptr && (g.N & 3) == 0 && batches == 1);
-    if (p.splits > 1 && (size_t)p.splits * g.M * g.N > ws_floats) p = make_plan(g.M, g.N, g.K, batches, false);
+    Plan p = make_plan(g.M, g.N, g.K, batches, allow_split && ws != nullptr && (g.N & 3) == 0 && batches == 1, a_kc && b_kc);
+    if (p.splits > 1 && (size_t)p.splits * g.M * g.N > ws_floats) p = make_plan(g.M, g.N, g.K, batches, false, a_kc && b_kc);
     g.k_per_split = p.k_per_split;
     g.tiles_m     = (g.M + kTiles[p.tile].bm - 1) / kTiles[p.tile].bm;
     g.tiles_n     = (g.N + kTiles[p.tile].bn - 1) / kTiles[p.tile].bn;

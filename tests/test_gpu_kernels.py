@@ -46,6 +46,20 @@ def test_gemm_fwd(M, N, K, epi):
     assert_close16(y, ref, 1e-3, max_ulp=1, what=f"fwd {M}x{N}x{K} {epi}")
 
 
+@pytest.mark.parametrize("M,N,K", [(512, 384, 256), (300, 576, 136), (256, 192, 64), (1024, 3072, 128)])
+def test_gemm_fwd_tile_256x192(M, N, K):
+    """The 256 x 192 tile (contraction-contiguous operands only), forced: interior and ragged variants."""
+    r = RNG(M + N + K + 5)
+    x, w, b = S16(r.standard_normal((M, K))), S16(r.standard_normal((N, K)) * 0.1), S16(r.standard_normal(N))
+    y = empty16(M, N)
+    mp.mp_gemm_tuning_override(8, 1)
+    try:
+        mp.mp_gemm_fwd(mp.gemm_desc(M, N, K, epilogue=2), h16(x), h16(w), h16(b), None, y)
+    finally:
+        mp.mp_gemm_tuning_override(-1, 0)
+    assert_close16(y, L.linear_fwd(MIXED, x, w, b, relu=True), 1e-3, max_ulp=1, what=f"fwd 256x192 tile {M}x{N}x{K}")
+
+
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
 def test_gemm_bwd_dx_and_dw(M, N, K):
     r = RNG(M * 3 + N + K)
