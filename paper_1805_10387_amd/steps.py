@@ -269,7 +269,7 @@ class TransformerStep(_StepBase):
             B.mp_gemm_bwd_dx(self.d_f2, dz2, w[p + "w2"], df, relu_src=a["f"], ld_aux=f)
             self._t("df", l, df)
             if self.grouped_dw:
-                B.mp_colsum(T, f, df, f, g[p + "b1"], st, ws)
+                fork(lambda wsx: B.mp_colsum(T, f, df, f, g[p + "b1"], st, wsx))
             else:
                 fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f1, df, a["y1"], g[p + "w1"], g[p + "b1"], st, wsx))
             B.mp_gemm_bwd_dx(self.d_f1, df, w[p + "w1"], self.dy1, add=dz2, ld_aux=d)
@@ -294,7 +294,7 @@ class TransformerStep(_StepBase):
                 B.mp_gemm_bwd_dw(self.d_s, self.dp, a["qkv"], dqkv[:, d:], None, None, ws)
             self._t("dqkv", l, dqkv)
             if self.grouped_dw:
-                B.mp_colsum(T, 3 * d, dqkv, 3 * d, g[p + "bqkv"], st, ws)
+                fork(lambda wsx: B.mp_colsum(T, 3 * d, dqkv, 3 * d, g[p + "bqkv"], st, wsx))
             else:
                 fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_qkv, dqkv, x, g[p + "wqkv"], g[p + "bqkv"], st, wsx))
             B.mp_gemm_bwd_dx(self.d_qkv, dqkv, w[p + "wqkv"], dx, add=dz1, ld_aux=d)

@@ -384,18 +384,24 @@ def test_config3_full_size_bench_configuration():
         assert O.unscale_check_update(MIXED, t, wl.opt, ost) == 0
         assert rel_fro(after["w32"][n], t[0]["w32"]) <= MASTER_TOL and rel_fro(after["m"][n], t[0]["m"]) <= MASTER_TOL
         assert np.array_equal(half_bits(after["w16"][n]), half_bits(MIXED.store(after["w32"][n])))
-    # graph replay == eager, several replays with eager work and synchronisation between them
+    # graph replay == eager, several replays with eager work and synchronisation between them; the replayed step is
+    # the two-stream one bench.py times (weight-gradient launch and bias-gradient column sums on a second stream),
+    # the eager one runs on a single stream: the bits must not depend on either
     eager = St.TransformerStep(wl, prechecked=True, flat_update=True)
     eager.set_batch(batch)
     eager.step()
-    graph = _graph_step(step)                     # capture = step 2 is recorded, not run
+    assert torch.equal(step.P.w32_arena, eager.P.w32_arena)
+    two = St.TransformerStep(wl, prechecked=True, flat_update=True, two_streams=True)
+    two.set_batch(batch)
+    two.step()
+    graph = _graph_step(two)                      # capture = step 2 is recorded, not run
     for _ in range(3):
         graph.replay()
         eager.step()
         torch.cuda.synchronize()
-        assert float(step.loss) == float(eager.loss)
-        assert torch.equal(step.P.w32_arena, eager.P.w32_arena) and torch.equal(step.P.w16_arena, eager.P.w16_arena)
-    s = step.state()
+        assert float(two.loss) == float(eager.loss)
+        assert torch.equal(two.P.w32_arena, eager.P.w32_arena) and torch.equal(two.P.w16_arena, eager.P.w16_arena)
+    s = two.state()
     assert (s.opt_step, s.skipped_steps, s.scale) == (4, 0, 2.0 ** 15)
 
 
@@ -403,7 +409,7 @@ def test_config3_full_size_scale_sequence_over_growth_interval():
     """120 iterations on the GPU; the recorded overflow flags replayed through the oracle's state machine must give
     the recorded scale sequence (growth at iteration 100), and no iteration may overflow."""
     wl = replace(I.C3, steps=120)
-    step = St.TransformerStep(wl, prechecked=True, flat_update=True)
+    step = St.TransformerStep(wl, prechecked=True, flat_update=True, two_streams=True)
     step.set_batch(wl.batch())
     step.step()
     graph = _graph_step(step)
