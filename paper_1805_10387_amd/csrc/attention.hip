@@ -138,14 +138,13 @@ __global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, 
             sum += e;
         }
     sum += __shfl_xor(sum, 32, 64);
-    const float inv = 1.0f / sum;  // one division per query; e * inv is within one fp32 ulp of e / sum
     unsigned pk[4][8];  // probabilities as fp16 pairs: pk[t][2q], pk[t][2q+1] = keys 32t + 8q + 4hf + {0,1},{2,3}
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
-            pk[t][2 * qd]     = pack2(acc[t][4 * qd] * inv, acc[t][4 * qd + 1] * inv);
-            pk[t][2 * qd + 1] = pack2(acc[t][4 * qd + 2] * inv, acc[t][4 * qd + 3] * inv);
+            pk[t][2 * qd]     = pack2(acc[t][4 * qd] / sum, acc[t][4 * qd + 1] / sum);
+            pk[t][2 * qd + 1] = pack2(acc[t][4 * qd + 2] / sum, acc[t][4 * qd + 3] / sum);
             const int n       = 32 * t + 8 * qd + 4 * hf;
             if (m < S && n < S) *reinterpret_cast<u32x2a*>(Pb + (long long)m * S + n) = u32x2a{pk[t][2 * qd], pk[t][2 * qd + 1]};
         }
