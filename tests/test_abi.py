@@ -68,6 +68,25 @@ def test_validation_errors_enqueue_nothing():
     assert lib.mp_unscale_check_update(None, 0, C.byref(cfg), 16, 0, None) == _lib.MP_E_INVAL
     assert lib.mp_layernorm_fwd(4, 12, 16, None, 16, 16, 1e-5, 16, 16, 16, None) == _lib.MP_E_UNSUPPORTED
     assert lib.mp_mse_scaled(4, 8, 16, 16, 4, 16, 16, 16, None, 0, None) == _lib.MP_E_INVAL      # ld < cols
+    # grouped weight gradients: empty / oversized lists, and shapes the grouped kernel does not take
+    assert lib.mp_gemm_bwd_dw_grouped(None, 0, None, None) == _lib.MP_E_INVAL
+    items = (_lib.GemmGroupItem * 9)()
+    assert lib.mp_gemm_bwd_dw_grouped(items, 9, None, None) == _lib.MP_E_INVAL
+    it = items[0]
+    it.desc.M, it.desc.N, it.desc.K, it.desc.ldx, it.desc.ldw, it.desc.ldy = 128, 136, 128, 128, 128, 136
+    it.desc.batch_outer = it.desc.batch_inner = 1
+    it.desc.alpha = 1.0
+    it.dY = it.X = it.dW = 256
+    assert lib.mp_gemm_bwd_dw_grouped(items, 1, None, None) == _lib.MP_E_UNSUPPORTED     # 136 is not a multiple of 128
+    assert b"mp_gemm_bwd_dw" in lib.mp_last_error()
+    it.desc.N, it.desc.ldy, it.dW = 128, 128, None
+    assert lib.mp_gemm_bwd_dw_grouped(items, 1, None, None) == _lib.MP_E_INVAL            # NULL operand
+    # matrix-core rate probe: buffers are checked before anything is launched
+    out = C.c_double(0.0)
+    assert lib.mp_mfma_sustained_rate(None, 0, None, 0, 1, 1, C.byref(out), None) == _lib.MP_E_INVAL
+    assert lib.mp_mfma_sustained_rate(256, 100, 256, 1 << 20, 256, 10, C.byref(out), None) == _lib.MP_E_INVAL   # too few operands
+    assert lib.mp_mfma_sustained_rate(256, 16384, 256, 10, 256, 10, C.byref(out), None) == _lib.MP_E_INVAL      # sink too small
+    assert lib.mp_mfma_sustained_rate(264, 16384, 256, 1 << 20, 256, 10, C.byref(out), None) == _lib.MP_E_INVAL  # misaligned
 
 
 def test_workspace_queries_are_consistent():

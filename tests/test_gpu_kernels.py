@@ -273,6 +273,19 @@ def test_gemm_grouped_flags_overflow_and_rejects_ragged_shapes():
     assert e.value.code == ML.MP_E_UNSUPPORTED
 
 
+def test_mfma_sustained_rate_probe_reads_sanely():
+    """The ceiling probe: all-zero operands run near the top clock, N(0,1) operands clearly below it, both far above
+    anything a memory-bound loop could show; the sink receives the (finite) accumulator sums."""
+    sink = empty32(256 * 256)
+    zeros = torch.zeros(16384, dtype=torch.float16, device="cuda")
+    normal = torch.randn(16384, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3)).half()
+    r0 = mp.mp_mfma_sustained_rate(zeros, sink, 256, 20000)
+    assert torch.all(sink == 0)
+    r1 = mp.mp_mfma_sustained_rate(normal, sink, 256, 20000)
+    assert torch.isfinite(sink).all()
+    assert 1000.0 < r1 < r0 < 2600.0, (r0, r1)
+
+
 def test_gemm_rejects_bad_arguments():
     d = mp.gemm_desc(8, 8, 8)
     with pytest.raises(mp.MPError) as e:
