@@ -165,6 +165,50 @@ def test_config1_free_running_sequence_and_masters():
         assert rel_fro(np32(step.P.w32[n]), tr.w32[n]) <= GRAD_TOL, n
 
 
+def test_config1_static_scale_that_is_not_a_power_of_two():
+    """Section 3.1 allows a constant loss scale of any value: S = 1000 for the whole run, the injected overflow
+    skips its step and leaves S alone.  Unscaling by a non-power-of-two is not exact, so this also exercises the
+    rounding of g / S on both sides."""
+    wl = replace(I.C1, scale=I.ScaleCfg(mode="static", init_scale=1000.0))
+    batch = wl.batch()
+    step = St.MLPStep(wl)
+    step.set_batch(batch)
+    teacher_forced(step, wl, Mo.mlp_fwd_bwd, batch, 10, inject_at=wl.inject_step, inject_name="w2",
+                   expect_found={wl.inject_step})
+    step = St.MLPStep(wl)
+    step.set_batch(batch)
+    tr, _ = free_running(step, wl, Mo.mlp_fwd_bwd, batch, 12, inject_at=wl.inject_step, inject_name="w2")
+    s = step.state()
+    assert [s.hist_scale[i] for i in range(12)] == [1000.0] * 12
+    assert (s.scale, s.opt_step, s.skipped_steps) == (1000.0, 11, 1)
+    for n in ("w1", "w2"):
+        assert rel_fro(np32(step.P.w32[n]), tr.w32[n]) <= MASTER_TOL, n
+
+
+def test_config1_exponentially_decaying_learning_rate():
+    """The learning rate is an argument of every optimizer call, so a schedule is host arithmetic: lr_k = lr_0 0.8^k
+    on both sides, masters compared after 12 steps (SGD: no sign-like amplification)."""
+    wl = I.C1
+    batch = wl.batch()
+    step = St.MLPStep(wl)
+    step.set_batch(batch)
+    w0 = _flat(wl)
+    tr = Mo.Trainer(MIXED, w0, wl.opt, wl.scale)
+    ob = Mo.island_batch(MIXED, batch)
+    for k in range(12):
+        lr = wl.opt.lr * 0.8 ** k
+        tr.opt = replace(wl.opt, lr=lr)
+        step.cfg.lr = lr
+        tr.step(Mo.mlp_fwd_bwd, ob)
+        step.step()
+    s = step.state()
+    assert (s.opt_step, s.skipped_steps, s.scale) == (tr.state.opt_step, tr.state.skipped_steps, tr.state.scale)
+    for n in ("w1", "w2"):
+        assert rel_fro(np32(step.P.w32[n]), tr.w32[n]) <= MASTER_TOL, n
+        assert rel_fro(np32(step.P.w32[n]) - w0[n], tr.w32[n] - w0[n]) <= GRAD_TOL, n  # the movement itself
+        assert np.array_equal(half_bits(np32(step.P.w16[n])), half_bits(MIXED.store(np32(step.P.w32[n]))))
+
+
 # ------------------------------------------------------------------ configs 2, 3
 def op_level_transformer(step, wl, batch, tol=GRAD_TOL, layers=None):
     """One forward/backward on the GPU with every stored tensor captured; each operation of the oracle is then
