@@ -413,3 +413,54 @@ class LSTMStep(_StepBase):
             B.mp_gemm_bwd_dw(self.d_gate_all[l], self.dgates, self.xh[l], g[f"l{l}.w"], g[f"l{l}.b"], self.st_grad, self.ws)
             above, ld_above = dxh, ldxh
         self.dx_input = above
+
+
+# ====================================================================================== command line
+def _main(argv=None):
+    """python -m paper_1805_10387_amd.steps <1..5> [--steps N] [--warmup W] [--graph]
+    Runs one of the five synthetic workloads for N timed iterations and prints one JSON line (ms per iteration,
+    tokens or rows per second, final loss and scale state).  Meant for profiling a workload under rocprofv3."""
+    import argparse
+    import json
+    import sys
+    import os
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import mp_inputs as I
+    ap = argparse.ArgumentParser(prog="python -m paper_1805_10387_amd.steps")
+    ap.add_argument("config", type=int, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--graph", action="store_true", help="replay the iteration as a HIP graph")
+    a = ap.parse_args(argv)
+    wl = {1: I.C1, 2: I.C2, 3: I.C3, 4: I.C4, 5: I.C5}[a.config]
+    # config 3 in the configuration bench.py times; the others as their parity tests run them
+    kw = dict(prechecked=True, flat_update=True) if a.config == 3 else {}
+    step = {1: MLPStep, 2: TransformerStep, 3: TransformerStep, 4: XentStep, 5: LSTMStep}[a.config](wl, **kw)
+    step.set_batch(wl.batch())
+    for _ in range(max(a.warmup, 1)):
+        step.step()
+    torch.cuda.synchronize()
+    run = step.step
+    if a.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step.step()
+        run = graph.replay
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(a.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    units = getattr(wl, "tokens", None) or getattr(wl, "rows", None) or 0
+    s = step.state()
+    print(json.dumps({"config": a.config, "ms_per_step": ms, "units_per_step": units, "units_per_s": units / (ms * 1e-3),
+                      "parameters": int(step.P.total), "launch": "HIP graph replay" if a.graph else "eager",
+                      "loss": float(step.loss), "loss_scale": s.scale, "opt_steps": s.opt_step, "skipped": s.skipped_steps}))
+
+
+if __name__ == "__main__":
+    _main()
