@@ -152,6 +152,20 @@ int mp_gemm_bwd_dx(const mp_gemm_desc* desc /* host */, const mp_half* dY, const
                    const mp_half* relu_src, const mp_half* add, int32_t ld_aux, mp_half* dX,
                    mp_stream stream);
 
+/* mp_gemm_fwd and mp_gemm_bwd_dx with a workspace (Section 3.1 arithmetic unchanged: fp16 operands, fp32 sums, one
+ * rounding).  A product with few output rows (the recurrent products of an LSTM: 32 rows) has too few output tiles
+ * to occupy the chip; given a workspace such a product splits its contraction over more workgroups (fp32 partial
+ * sums in ws, added in split order by a finish launch that applies scale, bias and the rounding).  Only products
+ * whose epilogue is none or bias, unbatched, without relu_src / add / acc_in / y_f32, are split; all others run
+ * exactly as without a workspace.  ws: device, 16-byte aligned, mp_gemm_split_workspace_bytes(desc) bytes (0: the
+ * plan does not split; NULL is then fine), contents irrelevant before and after.  A workspace that is too small
+ * is not an error: the product runs unsplit. */
+size_t mp_gemm_split_workspace_bytes(const mp_gemm_desc* desc);
+int    mp_gemm_fwd_ws(const mp_gemm_desc* desc, const mp_half* X, const mp_half* W, const mp_half* bias,
+                      const float* acc_in, mp_half* Y, float* y_f32, void* ws, size_t ws_bytes, mp_stream stream);
+int    mp_gemm_bwd_dx_ws(const mp_gemm_desc* desc, const mp_half* dY, const mp_half* W, const mp_half* relu_src,
+                         const mp_half* add, int32_t ld_aux, mp_half* dX, void* ws, size_t ws_bytes, mp_stream stream);
+
 /* dW = RNE16( alpha * dY^T X ) (overwrites; there is no gradient accumulation across calls) and,
  * if db != NULL, db[N] = RNE16( column sums of dY ) (unbatched only).
  *   st        device, or NULL: if given, st->found_inf is set when any value written to dW or db

@@ -59,6 +59,9 @@ SIGNATURES = {
     "mp_gemm_fwd": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, _P, _P, _P]),
     "mp_gemm_bwd_dx": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, C.c_int32, _P, _P]),
     "mp_gemm_bwd_dw": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mp_gemm_split_workspace_bytes": (_SZ, [C.POINTER(GemmDesc)]),
+    "mp_gemm_fwd_ws": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mp_gemm_bwd_dx_ws": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, C.c_int32, _P, _P, _SZ, _P]),
     "mp_gemm_bwd_dw_grouped": (_I, [C.POINTER(GemmGroupItem), _I, _P, _P]),
     "mp_gemm_tuning_override": (_I, [_I, _I]),
     "mp_colsum_workspace_bytes": (_SZ, [_I, _I]),

@@ -85,6 +85,24 @@ def mp_gemm_bwd_dx(desc: GemmDesc, dY, W, dX, relu_src=None, add=None, ld_aux=0)
     _check(L.load().mp_gemm_bwd_dx(C.byref(desc), _p(dY), _p(W), _p(relu_src), _p(add), ld_aux, _p(dX), _stream()))
 
 
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def mp_gemm_split_workspace_bytes(desc: GemmDesc) -> int:
+    return L.load().mp_gemm_split_workspace_bytes(C.byref(desc))
+
+
+def mp_gemm_fwd_ws(desc: GemmDesc, X, W, bias=None, acc_in=None, Y=None, y_f32=None, ws=None):
+    _check(L.load().mp_gemm_fwd_ws(C.byref(desc), _p(X), _p(W), _p(bias), _p(acc_in), _p(Y), _p(y_f32), _p(ws), _nbytes(ws),
+                                   _stream()))
+
+
+def mp_gemm_bwd_dx_ws(desc: GemmDesc, dY, W, dX, relu_src=None, add=None, ld_aux=0, ws=None):
+    _check(L.load().mp_gemm_bwd_dx_ws(C.byref(desc), _p(dY), _p(W), _p(relu_src), _p(add), ld_aux, _p(dX), _p(ws), _nbytes(ws),
+                                      _stream()))
+
+
 def mp_gemm_bwd_dw(desc: GemmDesc, dY, X, dW, db=None, st=None, ws=None):
     _check(L.load().mp_gemm_bwd_dw(C.byref(desc), _p(dY), _p(X), _p(dW), _p(db), _p(st), _p(ws),
                                    0 if ws is None else ws.numel() * ws.element_size(), _stream()))

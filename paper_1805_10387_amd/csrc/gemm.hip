@@ -572,8 +572,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_grouped_kernel(GroupArgs ga
 
 // Sum split-K partials in split order, scale, round once, optional non-finite flag.
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ part, int splits, long long mn,
-                                                            int N, int ldc, float alpha, uint16_t* __restrict__ C,
-                                                            int* found_inf) {
+                                                            int N, int ldc, float alpha, const uint16_t* __restrict__ bias,
+                                                            uint16_t* __restrict__ C, int* found_inf) {
     bool bad = false;
     for (long long v = (long long)blockIdx.x * 256 + threadIdx.x; v * 4 < mn; v += (long long)gridDim.x * 256) {
         const long long e = v * 4;  // N % 4 == 0 on this path
@@ -582,8 +582,12 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
             const float4 t = *reinterpret_cast<const float4*>(part + (long long)p * mn + e);
             s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
         }
-        const uint16_t  h0 = f2h(s.x * alpha), h1 = f2h(s.y * alpha), h2 = f2h(s.z * alpha), h3 = f2h(s.w * alpha);
         const long long m = e / N, n = e - m * N;
+        s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
+        if (bias) {
+            s.x += h2f(bias[n]); s.y += h2f(bias[n + 1]); s.z += h2f(bias[n + 2]); s.w += h2f(bias[n + 3]);
+        }
+        const uint16_t h0 = f2h(s.x), h1 = f2h(s.y), h2 = f2h(s.z), h3 = f2h(s.w);
         *reinterpret_cast<uint2*>(C + m * ldc + n) =
             make_uint2((unsigned)h0 | ((unsigned)h1 << 16), (unsigned)h2 | ((unsigned)h3 << 16));
         bad |= half_nonfinite(h0) | half_nonfinite(h1) | half_nonfinite(h2) | half_nonfinite(h3);
@@ -768,10 +772,11 @@ static int run_gemm(GemmArgs g, bool a_kc, bool b_kc, long long batches, bool al
     const dim3 grid((unsigned)gx, (unsigned)batches, (unsigned)p.splits);
 
     GemmArgs k = g;
-    if (p.splits > 1) {  // partials to workspace, epilogue in the finish kernel
+    if (p.splits > 1) {  // partials to workspace, epilogue (scale, bias, rounding, flag) in the finish kernel
         k.C32       = ws;
         k.C         = nullptr;
         k.found_inf = nullptr;
+        k.bias      = nullptr;
     }
     int rc;
     if (a_kc && b_kc) rc = launch_tile<true, true>(p.tile, k, grid, hs);
@@ -787,7 +792,7 @@ static int run_gemm(GemmArgs g, bool a_kc, bool b_kc, long long batches, bool al
         long long       nb = (mn / 4 + 255) / 256;
         if (nb > 4096) nb = 4096;
         hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)nb), dim3(256), 0, hs, ws, p.splits, mn, g.N, g.ldc, g.alpha,
-                           g.C, g.found_inf);
+                           g.bias, g.C, g.found_inf);
         MP_LAUNCH_CHECK("gemm (split-K finish)");
     }
     return MP_OK;
@@ -820,6 +825,12 @@ static size_t splitk_floats(int M, int N, int K) {
     return p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N : 0;
 }
 
+static size_t splitk_floats_any(int M, int N, int K, bool allow, bool kc_kc) {
+    if (M <= 0 || N <= 0 || (N & 3) != 0) return 0;
+    const Plan p = make_plan(M, N, K, 1, allow, kc_kc);
+    return p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N : 0;
+}
+
 extern "C" int mp_gemm_tuning_override(int tile, int splits) {
     MP_REQUIRE(tile < kNumTiles, "mp_gemm_tuning_override: tile index %d out of range (%d shapes)", tile, kNumTiles);
     g_force_tile   = tile;
@@ -836,8 +847,27 @@ extern "C" size_t mp_gemm_bwd_dw_workspace_bytes(const mp_gemm_desc* d, int with
     return b + 256;
 }
 
+// A product may split its contraction over grid.z (fp32 partials in `ws`, summed in split order by a finish launch)
+// when the epilogue is one the finish launch can do: scale, bias, one rounding, overflow flag.
+static bool split_ok(const GemmArgs& g, long long batches, const void* ws) {
+    return ws != nullptr && aligned16(ws) && batches == 1 && !g.relu && !g.relu_src && !g.add && !g.acc_in && !g.C32;
+}
+
+extern "C" size_t mp_gemm_split_workspace_bytes(const mp_gemm_desc* d) {
+    if (!d || d->M <= 0 || d->N <= 0 || d->K <= 0) return 0;
+    // the larger of the forward (M x N over K) and dX (M x K over N) plans; 0 when neither would split
+    const size_t a = splitk_floats_any(d->M, d->N, d->K, true, d->trans_w == 0);
+    const size_t b = splitk_floats_any(d->M, d->K, d->N, true, d->trans_w == 1);
+    return (a > b ? a : b) * sizeof(float);
+}
+
 extern "C" int mp_gemm_fwd(const mp_gemm_desc* d, const mp_half* X, const mp_half* W, const mp_half* bias,
                            const float* acc_in, mp_half* Y, float* y_f32, mp_stream stream) {
+    return mp_gemm_fwd_ws(d, X, W, bias, acc_in, Y, y_f32, nullptr, 0, stream);
+}
+
+extern "C" int mp_gemm_fwd_ws(const mp_gemm_desc* d, const mp_half* X, const mp_half* W, const mp_half* bias,
+                              const float* acc_in, mp_half* Y, float* y_f32, void* ws, size_t ws_bytes, mp_stream stream) {
     int rc = check_desc(d, "mp_gemm_fwd");
     if (rc) return rc;
     MP_REQUIRE(X && W && (Y || y_f32), "mp_gemm_fwd: NULL operand");
@@ -855,11 +885,18 @@ extern "C" int mp_gemm_fwd(const mp_gemm_desc* d, const mp_half* X, const mp_hal
     g.sa_o = d->sx_outer; g.sa_i = d->sx_inner; g.sb_o = d->sw_outer; g.sb_i = d->sw_inner;
     g.sc_o = d->sy_outer; g.sc_i = d->sy_inner;
     g.batch_inner = d->batch_inner; g.alpha = d->alpha;
-    return run_gemm(g, true, d->trans_w == 0, batches, false, nullptr, 0, as_stream(stream));
+    const bool sp = split_ok(g, batches, ws);
+    return run_gemm(g, true, d->trans_w == 0, batches, sp, sp ? static_cast<float*>(ws) : nullptr, sp ? ws_bytes / sizeof(float) : 0,
+                    as_stream(stream));
 }
 
 extern "C" int mp_gemm_bwd_dx(const mp_gemm_desc* d, const mp_half* dY, const mp_half* W, const mp_half* relu_src,
                               const mp_half* add, int32_t ld_aux, mp_half* dX, mp_stream stream) {
+    return mp_gemm_bwd_dx_ws(d, dY, W, relu_src, add, ld_aux, dX, nullptr, 0, stream);
+}
+
+extern "C" int mp_gemm_bwd_dx_ws(const mp_gemm_desc* d, const mp_half* dY, const mp_half* W, const mp_half* relu_src,
+                                 const mp_half* add, int32_t ld_aux, mp_half* dX, void* ws, size_t ws_bytes, mp_stream stream) {
     int rc = check_desc(d, "mp_gemm_bwd_dx");
     if (rc) return rc;
     MP_REQUIRE(dY && W && dX, "mp_gemm_bwd_dx: NULL operand");
@@ -874,7 +911,9 @@ extern "C" int mp_gemm_bwd_dx(const mp_gemm_desc* d, const mp_half* dY, const mp
     g.sc_o = d->sx_outer; g.sc_i = d->sx_inner;
     g.batch_inner = d->batch_inner; g.alpha = d->alpha;
     // W[N,K] read as B(n'=k, k'=n) is output-contiguous; W[K,N] is contraction-contiguous.
-    return run_gemm(g, true, d->trans_w == 1, (long long)d->batch_outer * d->batch_inner, false, nullptr, 0,
+    const long long batches = (long long)d->batch_outer * d->batch_inner;
+    const bool      sp      = split_ok(g, batches, ws);
+    return run_gemm(g, true, d->trans_w == 1, batches, sp, sp ? static_cast<float*>(ws) : nullptr, sp ? ws_bytes / sizeof(float) : 0,
                     as_stream(stream));
 }
 

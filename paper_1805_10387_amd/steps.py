@@ -377,6 +377,8 @@ class LSTMStep(_StepBase):
         self.d_gate = [B.gemm_desc(Bt, 4 * H, self.in_dims[l] + H, epilogue=ML.MP_EPI_BIAS) for l in range(NL)]
         self.d_gate_all = [B.gemm_desc(T * Bt, 4 * H, self.in_dims[l] + H) for l in range(NL)]
         need = [B.mp_gemm_bwd_dw_workspace_bytes(x, True) for x in self.d_gate_all] + [B.mp_loss_workspace_bytes(T * Bt, H)]
+        # the recurrent products have only `batch` rows: with a workspace they split their contraction over the chip
+        need += [B.mp_gemm_split_workspace_bytes(x) for x in self.d_gate]
         self._alloc_ws(max(need))
 
     def set_batch(self, batch):
@@ -391,7 +393,7 @@ class LSTMStep(_StepBase):
             I = self.in_dims[l]
             ldxh = I + H
             for t in range(T):
-                B.mp_gemm_fwd(self.d_gate[l], self.xh[l][t], w[f"l{l}.w"], w[f"l{l}.b"], None, self.gates[l][t])
+                B.mp_gemm_fwd_ws(self.d_gate[l], self.xh[l][t], w[f"l{l}.w"], w[f"l{l}.b"], None, self.gates[l][t], ws=self.ws)
                 if l + 1 < NL:
                     up, ldup = self.xh[l + 1][t], self.in_dims[l + 1] + H
                 else:
@@ -409,7 +411,7 @@ class LSTMStep(_StepBase):
                 rec = dxh[t + 1][:, I:] if t + 1 < T else None
                 B.mp_lstm_cell_bwd(Bt, H, self.gates[l][t], 4 * H, self.c[l][t], self.c[l][t + 1], above[t], ld_above,
                                    rec, ldxh, self.dc, self.dgates[t])
-                B.mp_gemm_bwd_dx(self.d_gate[l], self.dgates[t], w[f"l{l}.w"], dxh[t])
+                B.mp_gemm_bwd_dx_ws(self.d_gate[l], self.dgates[t], w[f"l{l}.w"], dxh[t], ws=self.ws)
             B.mp_gemm_bwd_dw(self.d_gate_all[l], self.dgates, self.xh[l], g[f"l{l}.w"], g[f"l{l}.b"], self.st_grad, self.ws)
             above, ld_above = dxh, ldxh
         self.dx_input = above

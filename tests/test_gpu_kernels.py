@@ -286,6 +286,32 @@ def test_mfma_sustained_rate_probe_reads_sanely():
     assert 1000.0 < r1 < r0 < 2600.0, (r0, r1)
 
 
+@pytest.mark.parametrize("M,N,K", [(32, 4096, 2048), (32, 1024, 512), (8, 2048, 4096), (48, 520, 1000)])
+def test_gemm_few_rows_with_workspace(M, N, K):
+    """Products with few output rows (the recurrent products of config 5) given a workspace: the contraction may be
+    split over more workgroups; forward with and without bias and dX against the oracle, also with a workspace that
+    is too small (runs unsplit) and with an epilogue that is never split (ReLU)."""
+    r = RNG(M + N + K + 17)
+    x, w, b = S16(r.standard_normal((M, K))), S16(r.standard_normal((N, K)) * 0.05), S16(r.standard_normal(N))
+    dy = S16(r.standard_normal((M, N)))
+    d0, d1, d2 = mp.gemm_desc(M, N, K), mp.gemm_desc(M, N, K, epilogue=1), mp.gemm_desc(M, N, K, epilogue=2)
+    need = mp.mp_gemm_split_workspace_bytes(d0)
+    if (M, N, K) == (32, 4096, 2048):
+        assert need > 0                                       # this one must split, or config 5 stays latency-bound
+    xd, wd, bd, dyd = h16(x), h16(w), h16(b), h16(dy)
+    for ws in (ws_bytes(max(need, 256)), ws_bytes(256), None):
+        y = empty16(M, N)
+        mp.mp_gemm_fwd_ws(d0, xd, wd, None, None, y, ws=ws)
+        assert_close16(y, L.linear_fwd(MIXED, x, w), 1e-3, max_ulp=1, what="few rows fwd")
+        mp.mp_gemm_fwd_ws(d1, xd, wd, bd, None, y, ws=ws)
+        assert_close16(y, L.linear_fwd(MIXED, x, w, b), 1e-3, max_ulp=1, what="few rows fwd + bias")
+        mp.mp_gemm_fwd_ws(d2, xd, wd, bd, None, y, ws=ws)
+        assert_close16(y, L.linear_fwd(MIXED, x, w, b, relu=True), 1e-3, max_ulp=1, what="few rows fwd + bias + relu")
+        dx = empty16(M, K)
+        mp.mp_gemm_bwd_dx_ws(d0, dyd, wd, dx, ws=ws)
+        assert_close16(dx, L.linear_bwd(MIXED, dy, x, w)[0], 1e-3, max_ulp=1, what="few rows dx")
+
+
 def test_gemm_rejects_bad_arguments():
     d = mp.gemm_desc(8, 8, 8)
     with pytest.raises(mp.MPError) as e:
