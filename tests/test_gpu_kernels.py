@@ -312,6 +312,39 @@ def test_gemm_few_rows_with_workspace(M, N, K):
         assert_close16(dx, L.linear_bwd(MIXED, dy, x, w)[0], 1e-3, max_ulp=1, what="few rows dx")
 
 
+def test_empty_and_degenerate_inputs():
+    """Zero rows: nothing is launched and the output is untouched.  Zero-length contraction: the sum is empty, the
+    epilogue still applies (Y = bias).  An empty tensor list and zero-length tensors in the optimizer wrapper: the step
+    counts as clean and the scale state advances like the oracle's."""
+    y = torch.full((4, 8), 3.0, dtype=torch.float16, device="cuda")
+    x, w = empty16(4, 8), empty16(8, 8)
+    mp.mp_gemm_fwd(mp.gemm_desc(0, 8, 8), x, w, None, None, y)
+    torch.cuda.synchronize()
+    assert torch.all(y == 3.0)
+    b = h16(S16(RNG(3).standard_normal(8)))
+    mp.mp_gemm_fwd(mp.gemm_desc(4, 8, 0, ldx=8, ldw=8, epilogue=1), x, w, b, None, y)
+    assert torch.equal(y, b.expand(4, 8))
+    dx = torch.full((4, 8), 5.0, dtype=torch.float16, device="cuda")
+    mp.mp_gemm_bwd_dx(mp.gemm_desc(4, 0, 8, ldy=8), empty16(4, 8), empty16(8, 8), dx)     # no output columns to contract over
+    assert torch.all(dx == 0)
+    st = make_state(interval=2)
+    cfg = mp.opt_cfg("adam", 1e-3)
+    mp.mp_unscale_check_update(None, 0, cfg, st)
+    mp.mp_loss_scale_update(st)
+    one = dict(g16=h16(np.ones(16, np.float32)), w32=f32(np.ones(16, np.float32)), w16=empty16(16), m=f32(np.zeros(16, np.float32)),
+               v=f32(np.zeros(16, np.float32)))
+    lst = mp.tensor_list([one, one])
+    lst[0].n = 0                                             # a zero-length tensor in front of a real one
+    mp.mp_unscale_check_update(lst, 2, cfg, st)
+    mp.mp_loss_scale_update(st)
+    s = mp.scale_state_read(st)
+    ost = O.ScaleState(scale=2.0 ** 15, growth_interval=2)
+    O.loss_scale_update(ost, 0)
+    O.loss_scale_update(ost, 0)
+    assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (ost.scale, ost.good_steps, ost.opt_step, 0) and s.scale == 2.0 ** 16
+    assert torch.all(one["w32"] < 1.0) and torch.equal(one["w16"], one["w32"].half())
+
+
 def test_gemm_rejects_bad_arguments():
     d = mp.gemm_desc(8, 8, 8)
     with pytest.raises(mp.MPError) as e:
