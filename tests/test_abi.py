@@ -3,6 +3,7 @@ mirror of the structs has the C layout, and argument validation rejects bad call
 import ctypes as C
 import os
 import re
+import sys
 
 import pytest
 
@@ -117,3 +118,11 @@ def test_product_never_imports_the_oracle():
         if fn.endswith(".py"):
             src = open(os.path.join(ROOT, "oracle", fn)).read()
             assert "paper_1805_10387_amd" not in src, fn
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N with N > 1 exits with a message before touching any device."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""

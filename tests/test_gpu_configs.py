@@ -542,3 +542,14 @@ def test_graph_replay_matches_eager_small():
         torch.cuda.synchronize()
         assert float(a.loss) == float(b.loss) and torch.equal(a.P.w32_arena, b.P.w32_arena)
     assert a.state().opt_step == b.state().opt_step == 5
+
+
+def test_workload_runner_command_line(capsys):
+    """python -m paper_1805_10387_amd.steps <n>: one JSON line per run, eager and as a graph replay."""
+    import json
+    St._main(["1", "--steps", "3", "--warmup", "1"])
+    St._main(["2", "--steps", "2", "--warmup", "1", "--graph"])
+    lines = [json.loads(l) for l in capsys.readouterr().out.strip().splitlines() if l.startswith("{")]
+    assert [l["config"] for l in lines] == [1, 2] and lines[1]["launch"] == "HIP graph replay"
+    assert all(l["ms_per_step"] > 0 and np.isfinite(l["loss"]) and l["skipped"] == 0 for l in lines)
+    assert lines[0]["opt_steps"] == 4 and lines[1]["opt_steps"] == 4          # warm-up + capture/first replay + timed
