@@ -168,7 +168,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
-              "How the step would shard over several GPUs is described in DESIGN.md.", file=sys.stderr)
+              "Sharding the step over several GPUs (one gradient exchange before the update) is designed, not built.", file=sys.stderr)
         sys.exit(2)
 
     import torch
