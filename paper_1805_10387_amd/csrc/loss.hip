@@ -64,12 +64,80 @@ __global__ __launch_bounds__(LOSS_THREADS) void mse_kernel(int rows, int cols, i
 }
 
 // ------------------------------------------------------------------------------- softmax cross-entropy
-// One workgroup per row.  With CACHE the row's fp16 bits stay in registers (<= 16 x 16 B per lane,
-// i.e. vocab <= 32768) so HBM sees one read and one write of the row; otherwise the row is
-// re-read (it then comes from L2).
-constexpr int XENT_MAXV = 16;
+// One workgroup per row.  Cached variant (vocab a multiple of 8, at most 32 x THREADS): every lane keeps its 32
+// logits in registers as fp32, overwrites them with exp(z - max) once and scales them on the way out, so HBM sees
+// one read and one write of the row and each exponential is computed once.  THREADS is picked from the row length
+// (256, 512 or 1024).  The generic variant re-reads the row (it then comes from L2).
+constexpr int XENT_VECS = 4;  // 16-byte vectors per lane
 
-template <bool CACHE>
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void xent_cached_kernel(int vocab, int ld, const uint16_t* logits,
+                                                              const int32_t* __restrict__ targets,
+                                                              const mp_scale_state* __restrict__ st, int rows,
+                                                              uint16_t* dlogits,  // may alias logits
+                                                              float* __restrict__ row_loss) {
+    __shared__ float red[THREADS / 64];
+    const int        row   = blockIdx.x;
+    const uint16_t*  z     = logits + (long long)row * ld;
+    uint16_t*        dz    = dlogits + (long long)row * ld;
+    const int        tgt   = targets[row];
+    const bool       valid = tgt >= 0 && tgt < vocab;
+    const float      coef  = valid ? (float)((double)st->scale / (double)rows) : 0.f;  // invalid target: zero gradient row
+    // read before the first barrier; every write to dlogits (which may alias logits) comes after it
+    const float      zt   = valid ? h2f(z[tgt]) : 0.f;
+    const int        nvec = vocab >> 3;
+    float            e[XENT_VECS][8];
+    float            mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < XENT_VECS; ++i) {
+        const int v = i * THREADS + threadIdx.x;
+        if (v < nvec) {
+            const uint4    c    = *reinterpret_cast<const uint4*>(z + (long long)v * 8);
+            const unsigned w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                e[i][2 * k]     = h2f((uint16_t)(w[k] & 0xFFFF));
+                e[i][2 * k + 1] = h2f((uint16_t)(w[k] >> 16));
+                mx              = fmaxf(mx, fmaxf(e[i][2 * k], e[i][2 * k + 1]));
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) e[i][k] = -INFINITY;
+        }
+    }
+    mx = block_max<THREADS / 64>(mx, red);
+    float se = 0.f;
+#pragma unroll
+    for (int i = 0; i < XENT_VECS; ++i)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            e[i][k] = __expf(e[i][k] - mx);  // exp(-inf) = 0 beyond the row
+            se += e[i][k];
+        }
+    se = block_sum<THREADS / 64>(se, red);
+    const float inv = 1.0f / se;
+    if (threadIdx.x == 0) row_loss[row] = valid ? (mx + __logf(se)) - zt : 0.f;
+    const int vt = valid ? (tgt >> 3) : -1;  // the vector that holds the target class
+#pragma unroll
+    for (int i = 0; i < XENT_VECS; ++i) {
+        const int v = i * THREADS + threadIdx.x;
+        if (v < nvec) {
+            float p[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) p[k] = e[i][k] * inv;
+            if (v == vt) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (k == (tgt & 7)) p[k] -= 1.0f;
+            }
+            unsigned o[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) o[k] = (unsigned)f2h(coef * p[2 * k]) | ((unsigned)f2h(coef * p[2 * k + 1]) << 16);
+            *reinterpret_cast<uint4*>(dz + (long long)v * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
 __global__ __launch_bounds__(LOSS_THREADS) void xent_kernel(int vocab, int ld, const uint16_t* logits,
                                                             const int32_t* __restrict__ targets,
                                                             const mp_scale_state* __restrict__ st, int rows,
@@ -84,75 +152,19 @@ __global__ __launch_bounds__(LOSS_THREADS) void xent_kernel(int vocab, int ld, c
     const float      coef = (float)((double)st->scale / (double)rows);
     // read before the first barrier; every write to dlogits (which may alias logits) comes after it
     const float      zt   = valid ? h2f(z[tgt]) : 0.f;
-
-    if (CACHE) {
-        const int nvec = vocab >> 3;
-        uint4     c[XENT_MAXV];
-        float     mx = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < XENT_MAXV; ++i) {
-            const int v = i * LOSS_THREADS + threadIdx.x;
-            if (v < nvec) {
-                c[i] = *reinterpret_cast<const uint4*>(z + (long long)v * 8);
-                const unsigned w[4] = {c[i].x, c[i].y, c[i].z, c[i].w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    mx = fmaxf(mx, h2f((uint16_t)(w[k] & 0xFFFF)));
-                    mx = fmaxf(mx, h2f((uint16_t)(w[k] >> 16)));
-                }
-            }
-        }
-        mx = block_max<LOSS_THREADS / 64>(mx, red);
-        float se = 0.f;
-#pragma unroll
-        for (int i = 0; i < XENT_MAXV; ++i) {
-            const int v = i * LOSS_THREADS + threadIdx.x;
-            if (v < nvec) {
-                const unsigned w[4] = {c[i].x, c[i].y, c[i].z, c[i].w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    se += __expf(h2f((uint16_t)(w[k] & 0xFFFF)) - mx);
-                    se += __expf(h2f((uint16_t)(w[k] >> 16)) - mx);
-                }
-            }
-        }
-        se = block_sum<LOSS_THREADS / 64>(se, red);
-        const float inv = 1.0f / se;
-        if (threadIdx.x == 0) row_loss[row] = valid ? (mx + __logf(se)) - zt : 0.f;
-#pragma unroll
-        for (int i = 0; i < XENT_MAXV; ++i) {
-            const int v = i * LOSS_THREADS + threadIdx.x;
-            if (v < nvec) {
-                const unsigned w[4] = {c[i].x, c[i].y, c[i].z, c[i].w};
-                unsigned       o[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int e0 = v * 8 + 2 * k;
-                    float     p0 = __expf(h2f((uint16_t)(w[k] & 0xFFFF)) - mx) * inv;
-                    float     p1 = __expf(h2f((uint16_t)(w[k] >> 16)) - mx) * inv;
-                    if (e0 == tgt) p0 -= 1.0f;
-                    if (e0 + 1 == tgt) p1 -= 1.0f;
-                    if (!valid) p0 = p1 = 0.f;
-                    o[k] = (unsigned)f2h(coef * p0) | ((unsigned)f2h(coef * p1) << 16);
-                }
-                *reinterpret_cast<uint4*>(dz + (long long)v * 8) = make_uint4(o[0], o[1], o[2], o[3]);
-            }
-        }
-    } else {
-        float mx = -INFINITY;
-        for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) mx = fmaxf(mx, h2f(z[e]));
-        mx = block_max<LOSS_THREADS / 64>(mx, red);
-        float se = 0.f;
-        for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) se += __expf(h2f(z[e]) - mx);
-        se = block_sum<LOSS_THREADS / 64>(se, red);
-        const float inv = 1.0f / se;
-        if (threadIdx.x == 0) row_loss[row] = valid ? (mx + __logf(se)) - zt : 0.f;
-        for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) {
-            float p = __expf(h2f(z[e]) - mx) * inv;
-            if (e == tgt) p -= 1.0f;
-            if (!valid) p = 0.f;
-            dz[e] = f2h(coef * p);
-        }
+    float mx = -INFINITY;
+    for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) mx = fmaxf(mx, h2f(z[e]));
+    mx = block_max<LOSS_THREADS / 64>(mx, red);
+    float se = 0.f;
+    for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) se += __expf(h2f(z[e]) - mx);
+    se = block_sum<LOSS_THREADS / 64>(se, red);
+    const float inv = 1.0f / se;
+    if (threadIdx.x == 0) row_loss[row] = valid ? (mx + __logf(se)) - zt : 0.f;
+    for (int e = threadIdx.x; e < vocab; e += LOSS_THREADS) {
+        float p = __expf(h2f(z[e]) - mx) * inv;
+        if (e == tgt) p -= 1.0f;
+        if (!valid) p = 0.f;
+        dz[e] = f2h(coef * p);
     }
 }
 
@@ -210,14 +222,21 @@ extern "C" int mp_softmax_xent_scaled(int rows, int vocab, const mp_half* logits
     }
     float*      row_loss = static_cast<float*>(ws);
     hipStream_t hs       = as_stream(stream);
-    const bool  cache = (vocab % 8 == 0) && (ld % 8 == 0) && aligned16(logits) && aligned16(dlogits) &&
-                       (vocab / 8 <= XENT_MAXV * LOSS_THREADS);
-    if (cache)
-        hipLaunchKernelGGL(xent_kernel<true>, dim3(rows), dim3(LOSS_THREADS), 0, hs, vocab, ld, logits, targets, st, rows,
-                           dlogits, row_loss);
+    const bool cache = (vocab % 8 == 0) && (ld % 8 == 0) && aligned16(logits) && aligned16(dlogits) &&
+                       (vocab / 8 <= XENT_VECS * 1024);
+    const int  nvec  = vocab / 8;
+    if (cache && nvec <= XENT_VECS * 256)
+        hipLaunchKernelGGL(xent_cached_kernel<256>, dim3(rows), dim3(256), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
+                           row_loss);
+    else if (cache && nvec <= XENT_VECS * 512)
+        hipLaunchKernelGGL(xent_cached_kernel<512>, dim3(rows), dim3(512), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
+                           row_loss);
+    else if (cache)
+        hipLaunchKernelGGL(xent_cached_kernel<1024>, dim3(rows), dim3(1024), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
+                           row_loss);
     else
-        hipLaunchKernelGGL(xent_kernel<false>, dim3(rows), dim3(LOSS_THREADS), 0, hs, vocab, ld, logits, targets, st, rows,
-                           dlogits, row_loss);
+        hipLaunchKernelGGL(xent_kernel, dim3(rows), dim3(LOSS_THREADS), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
+                           row_loss);
     MP_LAUNCH_CHECK("mp_softmax_xent_scaled");
     hipLaunchKernelGGL(finish_mean_kernel, dim3(1), dim3(LOSS_THREADS), 0, hs, row_loss, rows, (double)rows, loss);
     MP_LAUNCH_CHECK("mp_softmax_xent_scaled(finish)");
