@@ -6,10 +6,11 @@
  * fp32 master weights; Section 3.2: the optimizer wrapper; Section 3.3:
  * regularisation on the fp32 copy):
  *
- *   forward  : mp_gemm_fwd (+ mp_layernorm_fwd, mp_softmax_fwd, mp_lstm_cell_fwd)
+ *   forward  : mp_gemm_fwd[_ws] (+ mp_layernorm_fwd, mp_attention_fwd | mp_softmax_fwd,
+ *              mp_lstm_cell_fwd)
  *   loss     : mp_mse_scaled | mp_softmax_xent_scaled      (seed gradient x loss scale)
- *   backward : mp_gemm_bwd_dx, mp_gemm_bwd_dw (+ mp_layernorm_bwd, mp_softmax_bwd,
- *              mp_lstm_cell_bwd, mp_colsum)
+ *   backward : mp_gemm_bwd_dx[_ws], mp_gemm_bwd_dw | mp_gemm_bwd_dw_grouped (+ mp_layernorm_bwd,
+ *              mp_attention_bwd | mp_softmax_bwd, mp_lstm_cell_bwd, mp_colsum)
  *   update   : mp_unscale_check_update   (inspect fp16 gradients, unscale, SGD/Adam on
  *                                         fp32 masters, rewrite the fp16 copies - or skip)
  *              mp_loss_scale_update      (halve / count / grow the loss scale)
