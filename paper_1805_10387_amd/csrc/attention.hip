@@ -33,7 +33,21 @@ __device__ __forceinline__ f16x8 as_f16x8(u32x4a v) {
 __device__ __forceinline__ f16x8 join_f16x8(u32x2a lo, u32x2a hi) {
     union { u32x4a u; f16x8 h; } c; c.u = u32x4a{lo.x, lo.y, hi.x, hi.y}; return c.h;
 }
-__device__ __forceinline__ unsigned pack2(float a, float b) { return (unsigned)f2h(a) | ((unsigned)f2h(b) << 16); }
+__device__ __forceinline__ unsigned pack2(float a, float b) {  // RNE16 of both, one v_cvt_pk_f16_f32
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    typedef float    f2 __attribute__((ext_vector_type(2)));
+    const h2 h = __builtin_convertvector(f2{a, b}, h2);
+    return __builtin_bit_cast(unsigned, h);
+}
+
+// The matrix cores leave a lane (row lane%32, half hf) with packed pairs for columns 8 q + 4 hf + {0,1}, {2,3}.  Given the
+// pairs of q = 2c (a0, a1) and q = 2c + 1 (b0, b1), lanes r and r + 32 trade so that each ends up with 8 consecutive
+// columns, 16 c + 8 hf ... : 16-byte row pieces instead of 8-byte ones halve the cache accesses of a store.
+__device__ __forceinline__ u32x4a gather8(unsigned a0, unsigned a1, unsigned b0, unsigned b1) {
+    const auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+    const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+    return u32x4a{s0[0], s1[0], s0[1], s1[1]};
+}
 
 // 16 bytes = 8 consecutive head-dimension values of row `row` (rows >= rows_valid read as zero)
 __device__ __forceinline__ u32x4a load_row8(const uint16_t* base, int ld, int row, int rows_valid, int col) {
@@ -138,16 +152,23 @@ __global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, 
             sum += e;
         }
     sum += __shfl_xor(sum, 32, 64);
+    const float inv = 1.0f / sum;  // one division per query (the kernel is bound by vector ALU work); e * inv is within
+                                   // one fp32 ulp of e / sum, far inside the rounding to fp16 that follows
     unsigned pk[4][8];  // probabilities as fp16 pairs: pk[t][2q], pk[t][2q+1] = keys 32t + 8q + 4hf + {0,1},{2,3}
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t) {
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
-            pk[t][2 * qd]     = pack2(acc[t][4 * qd] / sum, acc[t][4 * qd + 1] / sum);
-            pk[t][2 * qd + 1] = pack2(acc[t][4 * qd + 2] / sum, acc[t][4 * qd + 3] / sum);
-            const int n       = 32 * t + 8 * qd + 4 * hf;
-            if (m < S && n < S) *reinterpret_cast<u32x2a*>(Pb + (long long)m * S + n) = u32x2a{pk[t][2 * qd], pk[t][2 * qd + 1]};
+            pk[t][2 * qd]     = pack2(acc[t][4 * qd] * inv, acc[t][4 * qd + 1] * inv);
+            pk[t][2 * qd + 1] = pack2(acc[t][4 * qd + 2] * inv, acc[t][4 * qd + 3] * inv);
         }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const u32x4a row8 = gather8(pk[t][4 * c], pk[t][4 * c + 1], pk[t][4 * c + 2], pk[t][4 * c + 3]);
+            const int    n    = 32 * t + 16 * c + 8 * hf;  // (S is a multiple of 8: a piece is inside or outside as a whole)
+            if (m < S && n < S) *reinterpret_cast<u32x4a*>(Pb + (long long)m * S + n) = row8;
+        }
+    }
     __syncthreads();  // Vt complete
 
     // ctx[m][d] = sum_n p[m][n] v[n][d]: A = Vt rows d, B = probability registers
@@ -172,10 +193,11 @@ __global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, 
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const int d = 32 * dt + 8 * qd + 4 * hf;
-                *reinterpret_cast<u32x2a*>(crow + d) =
-                    u32x2a{pack2(o[dt][4 * qd], o[dt][4 * qd + 1]), pack2(o[dt][4 * qd + 2], o[dt][4 * qd + 3])};
+            for (int c = 0; c < 2; ++c) {
+                const int q0 = 8 * c;  // accumulator registers of the column groups q = 2c, 2c + 1
+                *reinterpret_cast<u32x4a*>(crow + 32 * dt + 16 * c + 8 * hf) =
+                    gather8(pack2(o[dt][q0], o[dt][q0 + 1]), pack2(o[dt][q0 + 2], o[dt][q0 + 3]),
+                            pack2(o[dt][q0 + 4], o[dt][q0 + 5]), pack2(o[dt][q0 + 6], o[dt][q0 + 7]));
             }
     }
 }
@@ -275,10 +297,11 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    const int d = 32 * dt + 8 * qd + 4 * hf;
-                    *reinterpret_cast<u32x2a*>(row + d) = u32x2a{pack2(alpha * o[dt][4 * qd], alpha * o[dt][4 * qd + 1]),
-                                                                 pack2(alpha * o[dt][4 * qd + 2], alpha * o[dt][4 * qd + 3])};
+                for (int c = 0; c < 2; ++c) {
+                    const int q0 = 8 * c;
+                    *reinterpret_cast<u32x4a*>(row + 32 * dt + 16 * c + 8 * hf) =
+                        gather8(pack2(alpha * o[dt][q0], alpha * o[dt][q0 + 1]), pack2(alpha * o[dt][q0 + 2], alpha * o[dt][q0 + 3]),
+                                pack2(alpha * o[dt][q0 + 4], alpha * o[dt][q0 + 5]), pack2(alpha * o[dt][q0 + 6], alpha * o[dt][q0 + 7]));
                 }
         }
     }
@@ -312,10 +335,11 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
 #pragma unroll
                 for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                    for (int qd = 0; qd < 4; ++qd) {
-                        const int d = 32 * dt + 8 * qd + 4 * hf;
-                        *reinterpret_cast<u32x2a*>(row + d) = u32x2a{pack2(scale * o[dt][4 * qd], scale * o[dt][4 * qd + 1]),
-                                                                     pack2(scale * o[dt][4 * qd + 2], scale * o[dt][4 * qd + 3])};
+                    for (int c = 0; c < 2; ++c) {
+                        const int q0 = 8 * c;
+                        *reinterpret_cast<u32x4a*>(row + 32 * dt + 16 * c + 8 * hf) =
+                            gather8(pack2(scale * o[dt][q0], scale * o[dt][q0 + 1]), pack2(scale * o[dt][q0 + 2], scale * o[dt][q0 + 3]),
+                                    pack2(scale * o[dt][q0 + 4], scale * o[dt][q0 + 5]), pack2(scale * o[dt][q0 + 6], scale * o[dt][q0 + 7]));
                     }
             }
         }
