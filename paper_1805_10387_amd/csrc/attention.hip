@@ -89,10 +89,30 @@ __device__ __forceinline__ f16x8 t128_frag(const char* T, int row, int kk, int h
     return as_f16x8(*reinterpret_cast<const u32x4a*>(T + t128_off(row, 16 * kk + 8 * hf)));
 }
 
-// scores / dP tile product for one wave: D[n][m] = sum_d Arows[n][d] * Brows[m][d], operands read straight
-// from global memory (head dimension contiguous), m = 32 wave + lane%32, n over four 32-key tiles.
-__device__ __forceinline__ void rows_product(const uint16_t* An, int lda, const uint16_t* Bm, int ldb, int S, int wave,
-                                             int lane, f32x16 (&acc)[4]) {
+// Row-major staging: the workgroup copies a [rows_valid x 64] fp16 matrix M into LDS rows of 128 bytes (8 slots of 16
+// bytes, slot index XOR a function of the row, so that 32 consecutive rows read one logical slot without bank
+// conflicts); rows >= rows_valid become zero.  Loads are fully coalesced (8 lanes per 128-byte row), which the
+// matrix-core fragments (16 bytes of 32 different rows per instruction) are not: fetched straight from global memory
+// every fragment costs one cache access per 32 bytes, and every wave fetches the whole matrix again.
+__device__ __forceinline__ int r64_swz(int row) { return (row ^ (row >> 3)) & 7; }
+__device__ __forceinline__ void stage_rows(const uint16_t* M, int ld, int rows_valid, char* R) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int v = threadIdx.x + AT_THREADS * j;  // 1024 vectors of 8 columns
+        const int r = v >> 3, c = v & 7;
+        *reinterpret_cast<u32x4a*>(R + r * 128 + ((c ^ r64_swz(r)) << 4)) = load_row8(M, ld, r, rows_valid, c * 8);
+    }
+}
+// 8 consecutive columns 16 kk + 8 hf ... of staged row `row`
+__device__ __forceinline__ f16x8 rows_frag(const char* R, int row, int kk, int hf) {
+    return as_f16x8(*reinterpret_cast<const u32x4a*>(R + row * 128 + (((2 * kk + hf) ^ r64_swz(row)) << 4)));
+}
+
+// scores / dP tile product for one wave: D[n][m] = sum_d Arows[n][d] * Brows[m][d]; the key-side operand A (all 128
+// rows, used by every wave) comes from its staged copy in LDS, the query-side operand B (this wave's 32 rows, used
+// once) straight from global memory; m = 32 wave + lane%32, n over four 32-key tiles.
+__device__ __forceinline__ void rows_product(const char* An_lds, const uint16_t* Bm, int ldb, int S, int wave, int lane,
+                                             f32x16 (&acc)[4]) {
     const int hf = lane >> 5, m = 32 * wave + (lane & 31);
     f16x8     bq[4];
 #pragma unroll
@@ -103,10 +123,8 @@ __device__ __forceinline__ void rows_product(const uint16_t* An, int lda, const 
         if (32 * t < S) {  // wave-uniform
             const int n = 32 * t + (lane & 31);
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const f16x8 ak = as_f16x8(load_row8(An, lda, n, S, 16 * kk + 8 * hf));
-                acc[t]         = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak, bq[kk], acc[t], 0, 0, 0);
-            }
+            for (int kk = 0; kk < 4; ++kk)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rows_frag(An_lds, n, kk, hf), bq[kk], acc[t], 0, 0, 0);
         }
     }
 }
@@ -116,7 +134,8 @@ __global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, 
                                                                     int ld, int d_model, float alpha,
                                                                     uint16_t* __restrict__ P, uint16_t* __restrict__ ctx,
                                                                     int ld_ctx) {
-    extern __shared__ __align__(16) char smem[];  // Vt[64][128]
+    extern __shared__ __align__(16) char smem[];  // Vt[64][128] (16 KB), then the rows of K (16 KB)
+    char* Krows = smem + 64 * 256;
     const int b = blockIdx.x / n_heads, h = blockIdx.x - b * n_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
     const uint16_t* q = qkv + (long long)b * S * ld + h * AT_D;
@@ -124,10 +143,12 @@ __global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, 
     const uint16_t* v = q + 2 * d_model;
     uint16_t*       Pb = P + (long long)blockIdx.x * S * S;
 
+    stage_rows(k, ld, S, Krows);
     stage_transposed(v, ld, S, smem);  // Vt[d][n]
+    __syncthreads();                   // K rows (and Vt) complete
 
     f32x16 acc[4];
-    rows_product(k, ld, q, ld, S, wave, lane, acc);
+    rows_product(Krows, q, ld, S, wave, lane, acc);
 
     // softmax over the keys of query m; a lane holds 64 of its 128 scores, lane^32 the others
     const int m  = 32 * wave + (lane & 31);
@@ -169,7 +190,6 @@ __global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, 
             if (m < S && n < S) *reinterpret_cast<u32x4a*>(Pb + (long long)m * S + n) = row8;
         }
     }
-    __syncthreads();  // Vt complete
 
     // ctx[m][d] = sum_n p[m][n] v[n][d]: A = Vt rows d, B = probability registers
     f32x16 o[2];
@@ -228,10 +248,13 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
     uint16_t*       dv = dq + 2 * d_model;
 
     stage_transposed(k, ld, S, X);  // Kt
+    stage_rows(v, ld, S, Pt);       // the rows of V borrow the start of Pt until dP is done
+    __syncthreads();
 
     // dP[m][n] = sum_d dctx[m][d] v[n][d], same register layout as the scores (lane <-> query m)
     f32x16 acc[4];
-    rows_product(v, ld, dO, ld_ctx, S, wave, lane, acc);
+    rows_product(Pt, dO, ld_ctx, S, wave, lane, acc);
+    __syncthreads();                // every wave is done with the rows of V before Pt is written
 
     const int m = 32 * wave + (lane & 31);
     float     pr[4][16];
@@ -371,7 +394,7 @@ extern "C" int mp_attention_fwd(int n_seq, int n_heads, int seq_len, int d_head,
                                 float alpha, mp_half* p, mp_half* ctx, int ld_ctx, mp_stream stream) {
     int rc = attention_check("mp_attention_fwd", n_seq, n_heads, seq_len, d_head, qkv, ld_qkv, p, ctx, ld_ctx);
     if (rc) return rc;
-    hipLaunchKernelGGL(attention_fwd_kernel, dim3(n_seq * n_heads), dim3(AT_THREADS), 64 * 256, as_stream(stream), n_heads,
+    hipLaunchKernelGGL(attention_fwd_kernel, dim3(n_seq * n_heads), dim3(AT_THREADS), 64 * 256 + 128 * 128, as_stream(stream), n_heads,
                        seq_len, qkv, ld_qkv, n_heads * d_head, alpha, p, ctx, ld_ctx);
     MP_LAUNCH_CHECK("mp_attention_fwd");
     return MP_OK;
