@@ -262,19 +262,20 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-            const int n = 32 * t + 8 * qd + 4 * hf;
-            u32x2a    w = u32x2a{0u, 0u};
-            if (m < S && n < S) w = *reinterpret_cast<const u32x2a*>(Pb + (long long)m * S + n);
-            pr[t][4 * qd]     = h2f((uint16_t)(w.x & 0xFFFFu));
-            pr[t][4 * qd + 1] = h2f((uint16_t)(w.x >> 16));
-            pr[t][4 * qd + 2] = h2f((uint16_t)(w.y & 0xFFFFu));
-            pr[t][4 * qd + 3] = h2f((uint16_t)(w.y >> 16));
+        for (int c = 0; c < 2; ++c) {
+            // 16 bytes = keys 32t + 16c + 8hf ... of query m; lanes m and m + 32 then trade halves (gather8 is its own
+            // inverse) and hold keys 8q + 4hf + {0..3} for q = 2c (words 0, 1) and q = 2c + 1 (words 2, 3)
+            const int n8 = 32 * t + 16 * c + 8 * hf;
+            u32x4a    w  = u32x4a{0u, 0u, 0u, 0u};
+            if (m < S && n8 < S) w = *reinterpret_cast<const u32x4a*>(Pb + (long long)m * S + n8);
+            w = gather8(w[0], w[1], w[2], w[3]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float dp    = round16(acc[t][4 * qd + e]);  // dP is a stored tensor
-                acc[t][4 * qd + e] = dp;
-                inner += dp * pr[t][4 * qd + e];
+            for (int e = 0; e < 8; ++e) {
+                const int r = 8 * c + e;  // = 4 qd + (e % 4) with qd = 2c + e / 4
+                pr[t][r]    = h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu)));
+                const float dp = round16(acc[t][r]);  // dP is a stored tensor
+                acc[t][r]      = dp;
+                inner += dp * pr[t][r];
             }
         }
     inner += __shfl_xor(inner, 32, 64);
