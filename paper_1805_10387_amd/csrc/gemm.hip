@@ -201,14 +201,38 @@ struct LoaderSel { typedef KCLoader<R> T; };
 template <int R>
 struct LoaderSel<R, false> { typedef OCLoader<R> T; };
 
+// The operand stream of one workgroup: the two register sets per operand and the wave-uniform position of the next
+// k-tile to load.  It outlives a tile.  When the workgroup goes on to another tile of the same problem, the two loads
+// that would run past the end of the current tile fetch the first two k-tiles of the next one instead: that tile then
+// starts with its k-tile 0 in LDS stage 0 and its k-tile 1 on the way into (la1, lb1) (`primed`), without a prologue,
+// and those loads are queued ahead of the current tile's output stores instead of behind them.
+template <int BM, int BN, bool A_KC, bool B_KC>
+struct OperandStream {
+    typename LoaderSel<BM, A_KC>::T la0, la1;
+    typename LoaderSel<BN, B_KC>::T lb0, lb1;
+    const uint16_t *ta, *tb;  // origin of the next k-tile to load
+    int  k_next;              // its first k
+    bool primed;
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 bias[BN / 16];      // the coming tile's bias values for this lane's columns (4 per entry), when they start the sums
+    __device__ __forceinline__ void init(int lda, int ldb) {
+        la0.init(lda);
+        la1.init(lda);
+        lb0.init(ldb);
+        lb1.init(ldb);
+        ta = tb = nullptr;
+        k_next  = 0;
+        primed  = false;
+    }
+};
+
+// One output tile: tile number `pid` of problem g (tiles are numbered in bands of GROUP tile-rows), batch `by`, k-split
+// `bz` of `nz`; `pid_next` is the tile this workgroup takes afterwards (same problem, batch and split), or -1.
 // EDGE = false: every tile lies fully inside the matrices and K is a multiple of BK, so neither the
 // loads nor the stores carry bounds tests.  EDGE = true: every access is tested (ragged shapes).
-// One output tile: tile number `pid` of problem g (tiles are numbered in bands of GROUP tile-rows), batch `by`, k-split
-// `bz` of `nz`.  EDGE = false: every tile lies fully inside the matrices and K is a multiple of BK, so neither the
-// loads nor the stores carry bounds tests.  EDGE = true: every access is tested (ragged shapes).
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool EDGE>
-__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, const int by, const int bz, const int nz, char* smem,
-                                          bool& bad) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, const int pid_next, const int by, const int bz,
+                                          const int nz, char* smem, OperandStream<BM, BN, A_KC, B_KC>& S, bool& bad) {
     static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 matrix-core tiles per wave
@@ -225,14 +249,17 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
     const int kend = min(g.K, kbeg + g.k_per_split);
     const int nkt  = (kend - kbeg + BK - 1) / BK;
 
-    constexpr int GROUP = 4;
-    const int     band  = pid / (GROUP * g.tiles_n);
-    const int     first = band * GROUP;
-    const int     gsz   = min(GROUP, g.tiles_m - first);
-    const int     inb   = pid - band * GROUP * g.tiles_n;
-    const int     tile_m = first + inb % gsz;
-    const int     tile_n = inb / gsz;
-    const int     m0 = tile_m * BM, n0 = tile_n * BN;
+    auto tile_origin = [&](const int p, int& mm, int& nn) {
+        constexpr int GROUP = 4;
+        const int     band  = p / (GROUP * g.tiles_n);
+        const int     first = band * GROUP;
+        const int     gsz   = min(GROUP, g.tiles_m - first);
+        const int     inb   = p - band * GROUP * g.tiles_n;
+        mm                  = (first + inb % gsz) * BM;
+        nn                  = (inb / gsz) * BN;
+    };
+    int m0, n0;
+    tile_origin(pid, m0, n0);
 
 
     // The bias is a per-column constant of the fp32 sum, so it can start the accumulators (acc[i][j][4 q + c] is
@@ -245,13 +272,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (fold_bias) {
-        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    // (a primed stream brings the values along: they were requested ahead of the previous tile's output stores)
+    typedef unsigned u32x2b __attribute__((ext_vector_type(2)));
+    auto load_bias = [&](const int col0) {
         static_for<TN * 4>([&](auto tc) {
             constexpr int t = decltype(tc)::value, j = t / 4, q = t % 4;
-            const int     n = ncol + 32 * j + 8 * q + 4 * eh;  // 4 consecutive columns: one 8-byte load
-            u32x2         braw = {0u, 0u};
-            if (!EDGE || n < g.N) braw = *reinterpret_cast<const u32x2*>(g.bias + n);
+            const int     n = col0 + 32 * j + 8 * q + 4 * eh;  // 4 consecutive columns: one 8-byte load
+            S.bias[t]       = {0u, 0u};
+            if (!EDGE || n < g.N) S.bias[t] = *reinterpret_cast<const u32x2b*>(g.bias + n);
+        });
+    };
+    if (fold_bias) {
+        if (!S.primed) load_bias(ncol);
+        static_for<TN * 4>([&](auto tc) {
+            constexpr int t = decltype(tc)::value, j = t / 4, q = t % 4;
+            const auto    braw = S.bias[t];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float b = h2f((uint16_t)((e & 1) ? (braw[e >> 1] >> 16) : (braw[e >> 1] & 0xFFFFu)));
@@ -265,18 +300,29 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
     // work of tile t and are first needed (for the LDS store) after the work of tile t+1, so a load has
     // two compute phases to arrive.  With one workgroup per CU and one wave per SIMD nothing else hides
     // the memory latency.
-    typename LoaderSel<BM, A_KC>::T la0, la1;
-    typename LoaderSel<BN, B_KC>::T lb0, lb1;
-    la0.init(g.lda);
-    la1.init(g.lda);
-    lb0.init(g.ldb);
-    lb1.init(g.ldb);
     // wave-uniform tile origins, advanced by one k-step per load
-    const uint16_t* ta = A_KC ? A + (long long)m0 * g.lda + kbeg : A + (long long)kbeg * g.lda + m0;
-    const uint16_t* tb = B_KC ? B + (long long)n0 * g.ldb + kbeg : B + (long long)kbeg * g.ldb + n0;
     const long long step_a = A_KC ? BK : (long long)BK * g.lda;
     const long long step_b = B_KC ? BK : (long long)BK * g.ldb;
-    int             k_next = kbeg;  // first k of the next tile to load
+    auto origin_a = [&](const int mm) { return A_KC ? A + (long long)mm * g.lda + kbeg : A + (long long)kbeg * g.lda + mm; };
+    auto origin_b = [&](const int nn) { return B_KC ? B + (long long)nn * g.ldb + kbeg : B + (long long)kbeg * g.ldb + nn; };
+    if (!S.primed) {
+        S.ta     = origin_a(m0);
+        S.tb     = origin_b(n0);
+        S.k_next = kbeg;
+    }
+    // Where the stream goes behind this tile's last k-tile: on to the next tile (interior tiles with an even number of
+    // at least 4 k-tiles: the register sets and LDS stages then end the tile in the roles they start one in), or
+    // nowhere (see load_next).
+    const bool      chain = !EDGE && pid_next >= 0 && nkt >= 4 && (nkt & 1) == 0;
+    const uint16_t *nta = nullptr, *ntb = nullptr;
+    int             ncol1 = 0;
+    if (chain) {
+        int m1, n1;
+        tile_origin(pid_next, m1, n1);
+        nta   = origin_a(m1);
+        ntb   = origin_b(n1);
+        ncol1 = n1 + wn * WN;
+    }
 
     // matrix-core fragment addresses inside an LDS tile: row = base row + 32 i, k-slot = 2 kk + lane/32,
     // swizzled; only four distinct per-lane offsets exist (the rest are immediates), see swz().
@@ -288,16 +334,19 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
         offb[c] = brow * 128 + ((((2 * c) | (lane >> 5)) ^ swz(brow)) << 4);
     }
 
-    // Loads never branch in the interior variant: past the last k-tile the origin simply stops
+    // Loads never branch in the interior variant: past the last k-tile of the last tile the origin simply stops
     // advancing, so the (unused) extra loads re-read the last tile and stay in bounds.
     const int k_last = kbeg + (nkt > 0 ? nkt - 1 : 0) * BK;
+    auto advance = [&] {
+        const bool in = S.k_next < k_last;
+        S.ta     = in ? S.ta + step_a : (chain ? nta : S.ta);
+        S.tb     = in ? S.tb + step_b : (chain ? ntb : S.tb);
+        S.k_next = in ? S.k_next + BK : (chain ? kbeg : S.k_next);
+    };
     auto load_next = [&](auto& la, auto& lb) {
-        la.template load<EDGE>(ta, g.lda, g.M - m0, kend - k_next);
-        lb.template load<EDGE>(tb, g.ldb, g.N - n0, kend - k_next);
-        const bool adv = k_next < k_last;
-        ta += adv ? step_a : 0;
-        tb += adv ? step_b : 0;
-        k_next += adv ? BK : 0;
+        la.template load<EDGE>(S.ta, g.lda, g.M - m0, kend - S.k_next);
+        lb.template load<EDGE>(S.tb, g.ldb, g.N - n0, kend - S.k_next);
+        advance();
     };
     // One pipeline step: issue the global loads of a later tile into (ln_a, ln_b), multiply the tile in
     // LDS stage `sa` and store the tile held in (st_a, st_b) into LDS stage `da`.  In the interior
@@ -323,11 +372,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
             else
                 bf[kk & 1][f - TM] = *reinterpret_cast<const f16x8*>(sb + offb[kk ^ (((f - TM) & 1) << 1)] + (f - TM) * 4096);
         };
-        const int rows_a = g.M - m0, rows_b = g.N - n0, k_left = kend - k_next;
+        const int rows_a = g.M - m0, rows_b = g.N - n0, k_left = kend - S.k_next;
         auto gload = [&](auto gc) {
             constexpr int i = decltype(gc)::value;
-            if constexpr (i < NA) ln_a.template load_one<EDGE, i>(ta, g.lda, rows_a, k_left);
-            else ln_b.template load_one<EDGE, i - NA>(tb, g.ldb, rows_b, k_left);
+            if constexpr (i < NA) ln_a.template load_one<EDGE, i>(S.ta, g.lda, rows_a, k_left);
+            else ln_b.template load_one<EDGE, i - NA>(S.tb, g.ldb, rows_b, k_left);
         };
         auto lstore = [&](auto gc) {
             constexpr int i = decltype(gc)::value;
@@ -353,29 +402,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
             static_for<g1 - g0>([&](auto gc) { lstore(std::integral_constant<int, g0 + decltype(gc)::value>{}); });
             __builtin_amdgcn_sched_barrier(0);
         });
-        const bool adv = k_next < k_last;
-        ta += adv ? step_a : 0;
-        tb += adv ? step_b : 0;
-        k_next += adv ? BK : 0;
+        advance();
         __syncthreads();
     };
 
-    // prologue: tiles 0 and 1 into the two register sets, tile 0 on into LDS stage 0
-    load_next(la0, lb0);
-    load_next(la1, lb1);
-    la0.store(smem);
-    lb0.store(smem + A_BYTES);
-    __syncthreads();
+    // prologue (unless the previous tile of this workgroup left the stream primed): k-tiles 0 and 1 into the two
+    // register sets, k-tile 0 on into LDS stage 0
+    if (!S.primed) {
+        load_next(S.la0, S.lb0);
+        load_next(S.la1, S.lb1);
+        S.la0.store(smem);
+        S.lb0.store(smem + A_BYTES);
+        __syncthreads();
+    }
     // step kt multiplies tile kt out of stage kt&1, stores tile kt+1 (loaded one step earlier) into the
     // other stage and loads tile kt+2 into the register set tile kt came from.  Unrolled by two so that
     // the register sets have static names.  Loads and stores past the last tile are redundant but
-    // harmless (see load_next; the extra LDS store goes to the stage nobody reads any more).
+    // harmless (see load_next; the extra LDS store goes to the stage nobody reads any more), or belong to the next
+    // tile (chain).
     int kt = 0;
     for (; kt + 1 < nkt; kt += 2) {
-        step(la0, lb0, la1, lb1, smem, smem + STAGE);
-        step(la1, lb1, la0, lb0, smem + STAGE, smem);
+        step(S.la0, S.lb0, S.la1, S.lb1, smem, smem + STAGE);
+        step(S.la1, S.lb1, S.la0, S.lb0, smem + STAGE, smem);
     }
-    if (kt < nkt) step(la0, lb0, la1, lb1, smem, smem + STAGE);  // odd tile count
+    if (kt < nkt) step(S.la0, S.lb0, S.la1, S.lb1, smem, smem + STAGE);  // odd tile count
+    S.primed = chain;
+    if (chain && fold_bias) load_bias(ncol1);
 
     // ---- epilogue, in the layout the matrix cores leave the result in.  Of the 32x32 tile (i, j) lane
     // (er = lane % 32, eh = lane / 32) holds row er and, for q = 0..3, the 4 consecutive columns 8 q + 4 eh ...
@@ -515,13 +567,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
     // Persistent over tiles: workgroup w takes tiles w, w + gridDim.x, ...  The stores of one tile's epilogue
     // drain while the next tile's first loads are in flight.
     const int ntiles = g.tiles_m * g.tiles_n;
-    for (int vb = blockIdx.x; vb < ntiles; vb += gridDim.x) {
-        // consecutive ids are dispatched round-robin over the 8 XCDs (gridDim.x is a multiple of 8 whenever a
-        // workgroup takes more than one tile), so id -> (id % 8) * (ntiles / 8) + id / 8 gives each XCD, and its
-        // L2, a contiguous run of tiles
+    // consecutive ids are dispatched round-robin over the 8 XCDs (gridDim.x is a multiple of 8 whenever a
+    // workgroup takes more than one tile), so id -> (id % 8) * (ntiles / 8) + id / 8 gives each XCD, and its
+    // L2, a contiguous run of tiles
+    auto tile_of = [&](const int vb) {
         const int q = ntiles >> 3, rem = ntiles & 7, x = vb & 7, local = vb >> 3;
-        const int pid = x * q + min(x, rem) + local;
-        gemm_tile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, EDGE>(g, pid, blockIdx.y, blockIdx.z, gridDim.z, smem, bad);
+        return x * q + min(x, rem) + local;
+    };
+    OperandStream<BM, BN, A_KC, B_KC> S;
+    S.init(g.lda, g.ldb);
+    for (int vb = blockIdx.x; vb < ntiles; vb += gridDim.x) {
+        const int nvb = vb + gridDim.x;
+        gemm_tile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, EDGE>(g, tile_of(vb), nvb < ntiles ? tile_of(nvb) : -1, blockIdx.y,
+                                                             blockIdx.z, gridDim.z, smem, S, bad);
     }
     if (g.found_inf && __any(bad)) {
         if ((threadIdx.x & 63) == 0) atomicOr(g.found_inf, 1);
@@ -561,7 +619,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_grouped_kernel(GroupArgs ga
             }
         }
         bool bad = false;
-        gemm_tile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, false>(g, vb - first, 0, 0, 1, smem, bad);
+        OperandStream<BM, BN, A_KC, B_KC> S;
+        S.init(g.lda, g.ldb);
+        gemm_tile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, false>(g, vb - first, -1, 0, 0, 1, smem, S, bad);
         bad_any |= bad;
         __syncthreads();  // (tiles of different problems: keep the LDS stages of one tile apart from the next)
     }

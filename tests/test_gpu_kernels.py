@@ -60,6 +60,32 @@ def test_gemm_fwd_tile_256x192(M, N, K):
     assert_close16(y, L.linear_fwd(MIXED, x, w, b, relu=True), 1e-3, max_ulp=1, what=f"fwd 256x192 tile {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("tile,M,N,K", [(6, 1536, 1536, 1536), (6, 1536, 1536, 320), (6, 1536, 1536, 128),
+                                        (3, 2560, 3456, 512), (0, 4352, 4096, 256)])
+def test_gemm_workgroups_that_take_several_tiles(tile, M, N, K):
+    """More tiles than resident workgroups: a workgroup goes on to a second tile, and with an even number (>= 4) of
+    k-tiles the first k-tiles (and bias values) of that tile are fetched during the current one.  All three products,
+    with the epilogues that read a second operand."""
+    r = RNG(M + N + K + tile)
+    x, w, b = S16(r.standard_normal((M, K))), S16(r.standard_normal((N, K)) * 0.1), S16(r.standard_normal(N))
+    dy, src = S16(r.standard_normal((M, N))), S16(np.maximum(r.standard_normal((M, K)), 0))
+    d = mp.gemm_desc(M, N, K, epilogue=2)
+    y, dx, dw = empty16(M, N), empty16(M, K), empty16(N, K)
+    st = make_state()
+    ws = ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, False))
+    mp.mp_gemm_tuning_override(tile, 1)
+    try:
+        mp.mp_gemm_fwd(d, h16(x), h16(w), h16(b), None, y)
+        mp.mp_gemm_bwd_dx(mp.gemm_desc(M, N, K), h16(dy), h16(w), dx, relu_src=h16(src), ld_aux=K)
+        mp.mp_gemm_bwd_dw(mp.gemm_desc(M, N, K), h16(dy), h16(x), dw, None, st, ws)
+    finally:
+        mp.mp_gemm_tuning_override(-1, 0)
+    assert_close16(y, L.linear_fwd(MIXED, x, w, b, relu=True), 1e-3, max_ulp=1, what="fwd")
+    assert_close16(dx, L.relu_mask(MIXED, MIXED.store(dy @ w), src), 1e-3, max_ulp=1, what="dx")
+    assert_close16(dw, MIXED.store(dy.T @ x), 1e-3, max_ulp=1, what="dw")
+    assert mp.scale_state_read(st).found_inf == 0
+
+
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
 def test_gemm_bwd_dx_and_dw(M, N, K):
     r = RNG(M * 3 + N + K)
