@@ -705,7 +705,7 @@ static const TileCfg kTiles[] = {{256, 256, 1.00f}, {256, 128, 0.85f}, {128, 256
                                  {128, 64, 0.45f},  {64, 128, 0.45f},  {64, 64, 0.30f},   {32, 128, 0.25f},
                                  // only when both operands are stored contraction-contiguous (the transposing loader
                                  // wants a power-of-two tile edge): fills the chip evenly when N is a multiple of 192 only
-                                 {256, 192, 0.78f}};
+                                 {256, 192, 0.88f}};
 constexpr int   kTileKcOnly = 8;  // first index of the shapes restricted to that operand layout
 constexpr int   kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int   kCUs      = 256;
