@@ -130,7 +130,7 @@ __device__ __forceinline__ void rows_product(const char* An_lds, const uint16_t*
 }
 
 // ------------------------------------------------------------------------------------ forward
-__global__ __launch_bounds__(AT_THREADS) void attention_fwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
+__global__ __launch_bounds__(AT_THREADS, 4) void attention_fwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
                                                                     int ld, int d_model, float alpha,
                                                                     uint16_t* __restrict__ P, uint16_t* __restrict__ ctx,
                                                                     int ld_ctx) {
