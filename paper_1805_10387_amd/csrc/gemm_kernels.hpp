@@ -352,25 +352,31 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
     // variant this is one basic block, and the scheduling directives at its end interleave the memory
     // instructions with the matrix-core instructions (which run 8 passes each and leave the issue
     // port free): next-slice fragment reads right behind the first MFMAs of a slice, global loads
-    // and LDS stores spread evenly over the whole step.
+    // and LDS stores spread evenly over all slices but the last.
+    // The workgroup barrier of a step stands in front of its LAST slice: by then every wave has issued all its
+    // fragment reads of the stage being multiplied (the last slice's were issued a slice earlier) and all its stores
+    // into the other stage, so behind the barrier the other stage may be read and this one overwritten.  The last
+    // slice then runs out of registers while the first slice of the NEXT step is fetched from the other stage: a
+    // step starts with its first fragments in registers instead of waiting an LDS round trip for them.
+    constexpr int KS = BK / 16;   // k-slices per tile
+    constexpr int NR = TM + TN;   // fragment reads per slice
+    f16x8         af[2][TM], bf[2][TN];
+    // fragment f of slice kk of the stage at `stage` into buffer kk&1 (f < TM: A rows, else B rows)
+    auto read_frag = [&](const char* stage, auto kkc, auto fc) {
+        constexpr int kk = decltype(kkc)::value, f = decltype(fc)::value;
+        if constexpr (f < TM)
+            af[kk & 1][f] = *reinterpret_cast<const f16x8*>(stage + offa[kk ^ ((f & 1) << 1)] + f * 4096);
+        else
+            bf[kk & 1][f - TM] =
+                *reinterpret_cast<const f16x8*>(stage + A_BYTES + offb[kk ^ (((f - TM) & 1) << 1)] + (f - TM) * 4096);
+    };
     auto step = [&](auto& ln_a, auto& ln_b, const auto& st_a, const auto& st_b, const char* sa, char* da) {
-        const char* sb = sa + A_BYTES;
-        constexpr int KS = BK / 16;                                // k-slices per tile
         constexpr int MS = TM * TN;                                // matrix-core instructions per slice
         constexpr int NM = MS * KS;                                // ... per step
-        constexpr int NR = TM + TN;                                // fragment reads per slice
+        constexpr int NB = MS * (KS - 1);                          // ... in front of the barrier
         constexpr int NA = LoaderSel<BM, A_KC>::T::N_LOADS, NB_ = LoaderSel<BN, B_KC>::T::N_LOADS;
         constexpr int NG = NA + NB_;                               // global loads = LDS stores per step
         constexpr int RPM = (NR + MS - 1) / MS;                    // fragment reads issued behind one MFMA
-        f16x8 af[2][TM], bf[2][TN];
-        // fragment f of slice kk into buffer kk&1 (f < TM: A rows, else B rows)
-        auto read_frag = [&](auto kkc, auto fc) {
-            constexpr int kk = decltype(kkc)::value, f = decltype(fc)::value;
-            if constexpr (f < TM)
-                af[kk & 1][f] = *reinterpret_cast<const f16x8*>(sa + offa[kk ^ ((f & 1) << 1)] + f * 4096);
-            else
-                bf[kk & 1][f - TM] = *reinterpret_cast<const f16x8*>(sb + offb[kk ^ (((f - TM) & 1) << 1)] + (f - TM) * 4096);
-        };
         const int rows_a = g.M - m0, rows_b = g.N - n0, k_left = kend - S.k_next;
         auto gload = [&](auto gc) {
             constexpr int i = decltype(gc)::value;
@@ -382,27 +388,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
             if constexpr (i < NA) st_a.template store_one<i>(da);
             else st_b.template store_one<i - NA>(da + A_BYTES);
         };
-        static_for<NR>([&](auto fc) { read_frag(std::integral_constant<int, 0>{}, fc); });
         __builtin_amdgcn_sched_barrier(0);
         // Hand-placed order, pinned by scheduling barriers: behind matrix-core instruction m go the next
         // slice's fragment reads (at the start of a slice) and an even share of the step's global loads
         // and LDS stores.  An MFMA runs 8 passes and leaves the issue port free, so these overlap it.
         static_for<NM>([&](auto mc) {
             constexpr int m = decltype(mc)::value, kk = m / MS, q = m % MS, i = q / TN, j = q % TN;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
-            if constexpr (kk + 1 < KS) {
-                static_for<RPM>([&](auto rc) {
-                    constexpr int f = q * RPM + decltype(rc)::value;
-                    if constexpr (f < NR) read_frag(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, f>{});
-                });
+            if constexpr (m == NB) {
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
             }
-            constexpr int g0 = m * NG / NM, g1 = (m + 1) * NG / NM;
-            static_for<g1 - g0>([&](auto gc) { gload(std::integral_constant<int, g0 + decltype(gc)::value>{}); });
-            static_for<g1 - g0>([&](auto gc) { lstore(std::integral_constant<int, g0 + decltype(gc)::value>{}); });
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+            static_for<RPM>([&](auto rc) {
+                constexpr int f = q * RPM + decltype(rc)::value;
+                if constexpr (f < NR) {
+                    if constexpr (kk + 1 < KS) read_frag(sa, std::integral_constant<int, kk + 1>{}, std::integral_constant<int, f>{});
+                    else read_frag(da, std::integral_constant<int, 0>{}, std::integral_constant<int, f>{});  // next step
+                }
+            });
+            if constexpr (m < NB) {
+                constexpr int g0 = m * NG / NB, g1 = (m + 1) * NG / NB;
+                static_for<g1 - g0>([&](auto gc) { gload(std::integral_constant<int, g0 + decltype(gc)::value>{}); });
+                static_for<g1 - g0>([&](auto gc) { lstore(std::integral_constant<int, g0 + decltype(gc)::value>{}); });
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
         advance();
-        __syncthreads();
     };
 
     // prologue (unless the previous tile of this workgroup left the stream primed): k-tiles 0 and 1 into the two
@@ -419,6 +430,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
     // the register sets have static names.  Loads and stores past the last tile are redundant but
     // harmless (see load_next; the extra LDS store goes to the stage nobody reads any more), or belong to the next
     // tile (chain).
+    static_for<NR>([&](auto fc) { read_frag(smem, std::integral_constant<int, 0>{}, fc); });  // first slice of the first step
     int kt = 0;
     for (; kt + 1 < nkt; kt += 2) {
         step(S.la0, S.lb0, S.la1, S.lb1, smem, smem + STAGE);
