@@ -30,8 +30,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from the rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, each scaled by
 # what the same counter reads for the 256 MiB calibration copy below); the summaries with the commands are
 # profiles/gemm_update_config3_hbm_traffic.txt.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 170052863       # fetch 137.4 MB + write 32.6 MB, average over the launches of a step
-UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 2116336245    # fetch 1058.3 MB + write 1058.1 MB
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 170050219       # fetch 137.4 MB + write 32.6 MB, average over the launches of a step
+UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 2116335436    # fetch 1058.3 MB + write 1058.1 MB
 
 
 def _time_calls(torch, fn, reps):
