@@ -70,6 +70,25 @@ __global__ __launch_bounds__(LOSS_THREADS) void mse_kernel(int rows, int cols, i
 // (256, 512 or 1024).  The generic variant re-reads the row (it then comes from L2).
 constexpr int XENT_VECS = 4;  // 16-byte vectors per lane
 
+// Workgroup barrier that waits for the wave's LDS traffic only.  __syncthreads() also drains the wave's outstanding
+// global accesses (its fence covers the stores, and loads share their counter), which would make the loads of the next
+// row wait at every reduction of the current one.  The reductions below communicate through LDS alone.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+template <int NW, bool MAX>
+__device__ __forceinline__ float block_reduce_lds(float v, float* red) {
+    v = MAX ? wave_max(v) : wave_sum(v);
+    lds_barrier();  // everyone is done reading the previous result
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    lds_barrier();
+    float t = red[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) t = MAX ? fmaxf(t, red[i]) : t + red[i];
+    return t;
+}
+
+// Workgroups are persistent over rows (row = blockIdx.x, + gridDim.x, ...): the packed logits of the next row are
+// requested before the current row is reduced, so the two reductions and the exponentials of a row run under the
+// next row's memory latency.
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void xent_cached_kernel(int vocab, int ld, const uint16_t* logits,
                                                               const int32_t* __restrict__ targets,
@@ -77,64 +96,82 @@ __global__ __launch_bounds__(THREADS) void xent_cached_kernel(int vocab, int ld,
                                                               uint16_t* dlogits,  // may alias logits
                                                               float* __restrict__ row_loss) {
     __shared__ float red[THREADS / 64];
-    const int        row   = blockIdx.x;
-    const uint16_t*  z     = logits + (long long)row * ld;
-    uint16_t*        dz    = dlogits + (long long)row * ld;
-    const int        tgt   = targets[row];
-    const bool       valid = tgt >= 0 && tgt < vocab;
-    const float      coef  = valid ? (float)((double)st->scale / (double)rows) : 0.f;  // invalid target: zero gradient row
-    // read before the first barrier; every write to dlogits (which may alias logits) comes after it
-    const float      zt   = valid ? h2f(z[tgt]) : 0.f;
-    const int        nvec = vocab >> 3;
-    float            e[XENT_VECS][8];
-    float            mx = -INFINITY;
+    const int        nvec  = vocab >> 3;
+    const float      coef0 = (float)((double)st->scale / (double)rows);
+    // a row's packed logits, its target and the target's logit; vectors beyond the row read as -inf
+    auto fetch = [&](int row, uint4* q, int& tgt, float& zt) {
+        const uint16_t* z = logits + (long long)row * ld;
+        tgt               = targets[row];
+        zt                = (tgt >= 0 && tgt < vocab) ? h2f(z[tgt]) : 0.f;
 #pragma unroll
-    for (int i = 0; i < XENT_VECS; ++i) {
-        const int v = i * THREADS + threadIdx.x;
-        if (v < nvec) {
-            const uint4    c    = *reinterpret_cast<const uint4*>(z + (long long)v * 8);
-            const unsigned w[4] = {c.x, c.y, c.z, c.w};
+        for (int i = 0; i < XENT_VECS; ++i) {
+            const int v = i * THREADS + threadIdx.x;
+            q[i]        = make_uint4(0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u);
+            if (v < nvec) q[i] = *reinterpret_cast<const uint4*>(z + (long long)v * 8);
+        }
+    };
+    uint4 raw[XENT_VECS];
+    int   tgt = -1;
+    float zt  = 0.f;
+    int   row = blockIdx.x;
+    if (row < rows) fetch(row, raw, tgt, zt);
+    for (; row < rows; row += gridDim.x) {
+        // (the next row is another row of the same matrix: it is read before anything is written to it, also when
+        // dlogits aliases logits, because a row is only ever written by the workgroup that read it, afterwards)
+        uint4 nraw[XENT_VECS];
+        int   ntgt = -1;
+        float nzt  = 0.f;
+        if (row + (int)gridDim.x < rows) fetch(row + gridDim.x, nraw, ntgt, nzt);
+        uint16_t*   dz    = dlogits + (long long)row * ld;
+        const bool  valid = tgt >= 0 && tgt < vocab;
+        const float coef  = valid ? coef0 : 0.f;  // invalid target: zero gradient row
+        float       e[XENT_VECS][8];
+        float       mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < XENT_VECS; ++i) {
+            const unsigned w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 e[i][2 * k]     = h2f((uint16_t)(w[k] & 0xFFFF));
                 e[i][2 * k + 1] = h2f((uint16_t)(w[k] >> 16));
                 mx              = fmaxf(mx, fmaxf(e[i][2 * k], e[i][2 * k + 1]));
             }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) e[i][k] = -INFINITY;
         }
-    }
-    mx = block_max<THREADS / 64>(mx, red);
-    float se = 0.f;
+        mx = block_reduce_lds<THREADS / 64, true>(mx, red);
+        float se = 0.f;
 #pragma unroll
-    for (int i = 0; i < XENT_VECS; ++i)
+        for (int i = 0; i < XENT_VECS; ++i)
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            e[i][k] = __expf(e[i][k] - mx);  // exp(-inf) = 0 beyond the row
-            se += e[i][k];
-        }
-    se = block_sum<THREADS / 64>(se, red);
-    const float inv = 1.0f / se;
-    if (threadIdx.x == 0) row_loss[row] = valid ? (mx + __logf(se)) - zt : 0.f;
-    const int vt = valid ? (tgt >> 3) : -1;  // the vector that holds the target class
-#pragma unroll
-    for (int i = 0; i < XENT_VECS; ++i) {
-        const int v = i * THREADS + threadIdx.x;
-        if (v < nvec) {
-            float p[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) p[k] = e[i][k] * inv;
-            if (v == vt) {
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (k == (tgt & 7)) p[k] -= 1.0f;
+            for (int k = 0; k < 8; ++k) {
+                e[i][k] = __expf(e[i][k] - mx);  // exp(-inf) = 0 beyond the row
+                se += e[i][k];
             }
-            unsigned o[4];
+        se = block_reduce_lds<THREADS / 64, false>(se, red);
+        const float inv = 1.0f / se;
+        if (threadIdx.x == 0) row_loss[row] = valid ? (mx + __logf(se)) - zt : 0.f;
+        const int vt = valid ? (tgt >> 3) : -1;  // the vector that holds the target class
 #pragma unroll
-            for (int k = 0; k < 4; ++k) o[k] = (unsigned)f2h(coef * p[2 * k]) | ((unsigned)f2h(coef * p[2 * k + 1]) << 16);
-            *reinterpret_cast<uint4*>(dz + (long long)v * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+        for (int i = 0; i < XENT_VECS; ++i) {
+            const int v = i * THREADS + threadIdx.x;
+            if (v < nvec) {
+                float p[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) p[k] = e[i][k] * inv;
+                if (v == vt) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k)
+                        if (k == (tgt & 7)) p[k] -= 1.0f;
+                }
+                unsigned o[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o[k] = (unsigned)f2h(coef * p[2 * k]) | ((unsigned)f2h(coef * p[2 * k + 1]) << 16);
+                *reinterpret_cast<uint4*>(dz + (long long)v * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
         }
+#pragma unroll
+        for (int i = 0; i < XENT_VECS; ++i) raw[i] = nraw[i];
+        tgt = ntgt;
+        zt  = nzt;
     }
 }
 
@@ -209,6 +246,14 @@ extern "C" int mp_mse_scaled(int rows, int cols, const mp_half* y, const mp_half
     return MP_OK;
 }
 
+// Rows per workgroup: with 1024 lanes per row only one workgroup fits a CU (the kernel's registers allow 5 waves per
+// SIMD), and the workgroups are persistent so that the next row's loads overlap the current row's reductions (298 ->
+// 247 us at 8192 x 32768).  Shorter rows have several workgroups per CU to overlap with and run one row each.
+static int xent_grid(int rows, int threads) {
+    if (threads < 1024) return rows;
+    return rows < 256 ? rows : 256;
+}
+
 extern "C" int mp_softmax_xent_scaled(int rows, int vocab, const mp_half* logits, int ld, const int32_t* targets,
                                       const mp_scale_state* st, float* loss, mp_half* dlogits, void* ws,
                                       size_t ws_bytes, mp_stream stream) {
@@ -226,13 +271,13 @@ extern "C" int mp_softmax_xent_scaled(int rows, int vocab, const mp_half* logits
                        (vocab / 8 <= XENT_VECS * 1024);
     const int  nvec  = vocab / 8;
     if (cache && nvec <= XENT_VECS * 256)
-        hipLaunchKernelGGL(xent_cached_kernel<256>, dim3(rows), dim3(256), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
+        hipLaunchKernelGGL(xent_cached_kernel<256>, dim3(xent_grid(rows, 256)), dim3(256), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
                            row_loss);
     else if (cache && nvec <= XENT_VECS * 512)
-        hipLaunchKernelGGL(xent_cached_kernel<512>, dim3(rows), dim3(512), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
+        hipLaunchKernelGGL(xent_cached_kernel<512>, dim3(xent_grid(rows, 512)), dim3(512), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
                            row_loss);
     else if (cache)
-        hipLaunchKernelGGL(xent_cached_kernel<1024>, dim3(rows), dim3(1024), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
+        hipLaunchKernelGGL(xent_cached_kernel<1024>, dim3(xent_grid(rows, 1024)), dim3(1024), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
                            row_loss);
     else
         hipLaunchKernelGGL(xent_kernel, dim3(rows), dim3(LOSS_THREADS), 0, hs, vocab, ld, logits, targets, st, rows, dlogits,
