@@ -61,6 +61,12 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 // Sum over a block of NW waves; every thread gets the result.  `red` is NW floats of LDS.
+// Workgroup barrier that waits for the wave's LDS traffic only.  __syncthreads() is also a release fence: with global
+// stores outstanding it waits for them to complete, and for every load issued before it, since loads and stores share
+// one counter.  Where the waves of a workgroup communicate through LDS alone this barrier is enough, and global
+// accesses stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int NW>
 __device__ __forceinline__ float block_sum(float v, float* red) {
     v = wave_sum(v);

@@ -70,10 +70,6 @@ __global__ __launch_bounds__(LOSS_THREADS) void mse_kernel(int rows, int cols, i
 // (256, 512 or 1024).  The generic variant re-reads the row (it then comes from L2).
 constexpr int XENT_VECS = 4;  // 16-byte vectors per lane
 
-// Workgroup barrier that waits for the wave's LDS traffic only.  __syncthreads() also drains the wave's outstanding
-// global accesses (its fence covers the stores, and loads share their counter), which would make the loads of the next
-// row wait at every reduction of the current one.  The reductions below communicate through LDS alone.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 template <int NW, bool MAX>
 __device__ __forceinline__ float block_reduce_lds(float v, float* red) {
     v = MAX ? wave_max(v) : wave_sum(v);
