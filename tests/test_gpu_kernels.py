@@ -398,7 +398,8 @@ def test_mse_scaled(rows, cols):
     assert_close16(dy, dy_ref, 1e-3, max_ulp=1, what="mse dy")
 
 
-@pytest.mark.parametrize("rows,vocab", [(16, 32768), (33, 3000), (7, 1001), (5, 40000)])
+@pytest.mark.parametrize("rows,vocab", [(16, 32768), (33, 3000), (7, 1001), (5, 40000),
+                                        (600, 32768), (300, 24584)])  # the last two: several rows per persistent workgroup
 def test_softmax_xent_scaled(rows, vocab):
     r = RNG(rows + vocab)
     z = S16(r.standard_normal((rows, vocab)) * 3)
