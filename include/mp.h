@@ -30,7 +30,14 @@
  *     graph.
  *   - Return value: MP_OK or a negative error code; mp_last_error() gives a
  *     thread-local human-readable message for the last failure on this thread.
- *     A call that returns an error has enqueued nothing.
+ *     Argument errors (MP_E_INVAL, MP_E_UNSUPPORTED, MP_E_WORKSPACE) are found before
+ *     anything is enqueued.  MP_E_HIP from an entry point that makes several launches
+ *     (split contractions, column sums, the update over many tensors) may leave the
+ *     earlier launches enqueued: treat the outputs as undefined.
+ *   - The library keeps no state between calls, with two documented exceptions that are
+ *     measurement aids and not part of a training step: mp_gemm_tuning_override (a
+ *     process-wide, not thread-safe tile choice for sweeps) and mp_mfma_sustained_rate
+ *     (the ONE call that blocks: it times its own launch with events).
  *   - Scratch ("workspace") is caller-provided device memory; each call that needs it
  *     has a *_workspace_bytes query.  Contents need not be initialised and are
  *     undefined afterwards.  Calls sharing one workspace must be on one stream.
@@ -89,8 +96,8 @@ typedef struct mp_scale_state {
 int mp_scale_state_init(mp_scale_state* st, int mode, float init_scale, int growth_interval,
                         float min_scale, float max_scale, mp_stream stream);
 
-/* End of an iteration ("the optimizer inspects gradients at each iteration and scales the loss for
- * the next iteration", Section 3.1).  Reads st->found_inf and then, on the device:
+/* End of an iteration (Section 3.1 item 1: the gradients inspected in this iteration decide the
+ * scale of the next one).  Reads st->found_inf and then, on the device:
  *   log (S, found_inf); total_steps++
  *   overflow : skipped_steps++, good_steps = 0, BACKOFF: S = max(S/2, min_scale)
  *   clean    : opt_step++, good_steps++, BACKOFF and good_steps == growth_interval:
@@ -192,10 +199,14 @@ typedef struct mp_gemm_group_item {
 } mp_gemm_group_item;
 int mp_gemm_bwd_dw_grouped(const mp_gemm_group_item* items, int count, mp_scale_state* st, mp_stream stream);
 
-/* Tuning aid, process-wide and not thread-safe: force every following contraction onto tile shape `tile`
+/* Tuning aid for sweeps and tests, process-wide and not thread-safe (the one piece of mutable library state;
+ * a training step never calls it): force every following contraction onto tile shape `tile`
  * (index into the library's tile table: 0 = 256x256, 1 = 256x128, 2 = 128x256, 3 = 128x128, 4 = 128x64,
- * 5 = 64x128, 6 = 64x64, 7 = 32x128) and, where splitting the contraction is allowed, onto `splits` splits.
- * tile < 0 restores the built-in choice.  Results do not depend on it beyond fp32 summation order.
+ * 5 = 64x128, 6 = 64x64, 7 = 32x128, 8 = 256x192 for products whose operands are both stored
+ * contraction-contiguous, else 256x256) and, where splitting the contraction is allowed, onto `splits`
+ * (0..16; 0 = 1) splits, reduced until every split owns at least one k-tile.  tile >= the table size or splits
+ * outside 0..16: MP_E_INVAL.  tile < 0 restores the built-in choice.  Results do not depend on it beyond fp32
+ * summation order.
  * Note that mp_gemm_bwd_dw_workspace_bytes answers for the choice in force when it is called. */
 int mp_gemm_tuning_override(int tile, int splits);
 
@@ -300,7 +311,7 @@ int mp_fill_u32(size_t n, uint32_t value, void* dst, mp_stream stream);
  * operand registers of every lane; zeros, or values distributed like the tensors of interest: the clock the chip
  * holds under this load depends on them).  sink: device, >= workgroups * 256 floats, receives the accumulator
  * sums.  tflops: host, receives 2 * 32 * 32 * 16 flops per instruction over the time between two events on
- * `stream`.  Blocks until the timed launch has finished.  Errors: MP_E_INVALID for NULL / short / misaligned
+ * `stream`.  Blocks until the timed launch has finished (the only call that does).  Errors: MP_E_INVAL for NULL / short / misaligned
  * buffers or counts out of range. */
 int mp_mfma_sustained_rate(const mp_half* operands, size_t n_operands, float* sink, size_t n_sink, int workgroups,
                            int iters, double* tflops, mp_stream stream);

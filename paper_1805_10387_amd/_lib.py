@@ -5,8 +5,7 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# MP_LIBMP_PATH lets a developer load another build of the same library (e.g. an experiment)
-LIB_PATH = os.environ.get("MP_LIBMP_PATH") or os.path.join(HERE, "libmp.so")
+LIB_PATH = os.path.join(HERE, "libmp.so")   # the in-tree build, and nothing else
 
 MP_HISTORY = 4096
 MP_OK, MP_E_INVAL, MP_E_UNSUPPORTED, MP_E_WORKSPACE, MP_E_HIP = 0, -1, -2, -3, -4

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g, int a_kc,
             g.C32[(long long)m * g.N + n] = acc;
         } else {
             if (g.bias) acc += h2f(g.bias[n]);
-            if (g.relu) acc = fmaxf(acc, 0.f);
+            if (g.relu) acc = (acc < 0.f) ? 0.f : acc;  // keeps a NaN, like the definition max(x, 0) on the reals extended by NaN
             uint16_t        h = f2h(acc);
             const long long coff = bo * g.sc_o + bi * g.sc_i;
             if (g.relu_src) {
@@ -105,7 +105,13 @@ static Plan make_plan(int M, int N, int K, long long batches, bool allow_split, 
     if (g_force_tile >= 0) {
         int t = g_force_tile < (kc_kc ? kNumTiles : kTileKcOnly) ? g_force_tile : 0, sp = allow_split ? g_force_splits : 1;
         if (sp < 1) sp = 1;
-        const int kps = ((K + sp - 1) / sp + BK - 1) / BK * BK;
+        if (sp > 16) sp = 16;
+        // every split must own at least one k-tile: (sp - 1) * k_per_split < K, as in the planner's own search
+        int kps = ((K + sp - 1) / sp + BK - 1) / BK * BK;
+        while (sp > 1 && (long long)(sp - 1) * kps >= K) {
+            --sp;
+            kps = ((K + sp - 1) / sp + BK - 1) / BK * BK;
+        }
         return Plan{t, sp, kps > 0 ? kps : BK};
     }
     Plan   best{0, 1, 0};
@@ -237,6 +243,7 @@ static size_t splitk_floats_any(int M, int N, int K, bool allow, bool kc_kc) {
 
 extern "C" int mp_gemm_tuning_override(int tile, int splits) {
     MP_REQUIRE(tile < kNumTiles, "mp_gemm_tuning_override: tile index %d out of range (%d shapes)", tile, kNumTiles);
+    MP_REQUIRE(tile < 0 || (splits >= 0 && splits <= 16), "mp_gemm_tuning_override: splits %d outside 0..16", splits);
     g_force_tile   = tile;
     g_force_splits = splits > 0 ? splits : 1;
     return MP_OK;

@@ -1,5 +1,5 @@
-// fp16 x fp16 -> fp32-accumulate contractions on the gfx950 matrix cores (paper Section 3.1:
-// "math is done in FP16, results are accumulated in FP32"), with one RNE rounding to fp16 in the
+// fp16 x fp16 -> fp32-accumulate contractions on the gfx950 matrix cores (the arithmetic of the paper's
+// Section 3.1: half-precision operands, single-precision sums), with one RNE rounding to fp16 in the
 // epilogue.
 //
 // One kernel template serves forward, input-gradient and weight-gradient products.  Internally a
@@ -515,7 +515,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
                 for (int e = 0; e < 16; ++e) v[e] = acc_get(acc[i][j][e]);
                 if (g.relu) {
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) v[e] = __builtin_amdgcn_fmed3f(v[e], 0.f, __builtin_inff());  // max(v, 0), NaN -> 0
+                    for (int e = 0; e < 16; ++e) v[e] = (v[e] < 0.f) ? 0.f : v[e];  // max(v, 0) that keeps a NaN (the comparison is false for it)
                 }
                 // one rounding to fp16, packed in pairs: d[2 q], d[2 q + 1] = columns 8 q + 4 eh + {0, 1}, {2, 3}
                 unsigned d[8];

@@ -45,7 +45,7 @@ def _f64(d):
 
 
 def teacher_forced(step, wl, fwd_bwd, batch, n_steps, inject_at=None, inject_name=None, expect_found=(),
-                   loss_tol=2e-4, batch_fn=None, grad_mode="direct"):
+                   loss_tol=2e-4, batch_fn=None, grad_mode="direct", progress=None):
     """grad_mode "direct": whole-network gradients within GRAD_TOL of the oracle's (holds where the network
     has no discontinuity between the compared tensors and identical inputs).  "vs_fp64": for deep ReLU
     stacks a 1-ulp difference in a stored activation flips ReLU masks and moves whole-network gradients by
@@ -111,6 +111,8 @@ def teacher_forced(step, wl, fwd_bwd, batch, n_steps, inject_at=None, inject_nam
             assert np.array_equal(half_bits(after["w16"][n]), half_bits(MIXED.store(after["w32"][n]))), f"w16 != RNE16(w32) for {n}"
             if after["m"]:
                 assert rel_fro(after["m"][n], t["m"]) <= MASTER_TOL and rel_fro(after["v"][n], t["v"]) <= MASTER_TOL
+        if progress:
+            print(f"{progress}: step {k} loss {float(step.loss):.5f} worst so far {worst}", flush=True)
     return worst
 
 
@@ -137,6 +139,13 @@ def free_running(step, wl, fwd_bwd, batch, n_steps, inject_at=None, inject_name=
     assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (tr.state.scale, tr.state.good_steps, tr.state.opt_step, tr.state.skipped_steps)
     assert np.allclose(losses, tr.losses, rtol=loss_tol, equal_nan=True), (losses, tr.losses)
     return tr, losses
+
+
+def _graph_step(step):
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step.step()
+    return g
 
 
 # ------------------------------------------------------------------ config 1 (full size)
@@ -345,6 +354,89 @@ def test_config3_reduced_prechecked_flat_update_matches_default():
     assert float(a.loss) == float(b.loss)
 
 
+def _assert_clean_steps_have_margin(step, lo=0.55, hi=0.8):
+    """The largest finite |gradient| of a clean step, as a fraction of the fp16 maximum.  Inside (lo, hi) the skip
+    decisions of a run are not a matter of summation order: the same step one scale doubling up overflows by more than
+    10 %, and stays clean by more than 20 %, where the two sides differ by about 1e-3."""
+    g = step.P.g16_arena.float()
+    m = float(g[torch.isfinite(g)].abs().max()) / 65504.0
+    assert lo < m < hi, f"clean step with max |g| = {m:.3f} of the fp16 range: the overflow pattern of this run is fragile"
+
+
+def test_config3_reduced_overflowing_run_in_the_bench_configuration():
+    """Producer-side overflow inspection + one flat update descriptor + second stream (the configuration bench.py
+    times) on a run that overflows NATURALLY: the start scale 2^24 is three halvings too high, and with a growth
+    interval of 3 every fourth clean step doubles the scale back into overflow.  Flags, skipped steps and the scale
+    sequence must equal the free-running oracle's; a graph replay of the same run must give the eager run's bits."""
+    wl = replace(I.C3_SMALL, scale=I.ScaleCfg(init_scale=2.0 ** 24, growth_interval=3))
+    f = Mo.make_transformer_fwd_bwd(wl.n_layers, wl.n_seq, wl.seq_len, wl.n_heads)
+    batch = wl.batch()
+    n = 12
+    step = St.TransformerStep(wl, prechecked=True, flat_update=True, two_streams=True)
+    step.set_batch(batch)
+    tr = Mo.Trainer(MIXED, _flat(wl), wl.opt, wl.scale)
+    ob = Mo.island_batch(MIXED, batch)
+    for k in range(n):
+        tr.step(f, ob)
+        before = step.P.w32_arena.clone()
+        step.forward_backward()
+        torch.cuda.synchronize()
+        found = int(step.state().found_inf)                  # set by the gradient producers, before any inspection pass
+        assert found == tr.state.history[k][1], f"step {k}: producers flagged {found}, oracle {tr.state.history[k][1]}"
+        if not found:
+            _assert_clean_steps_have_margin(step)
+        step.optimizer()
+        assert torch.equal(before, step.P.w32_arena) == bool(found), f"step {k}: skip decision"
+    s = step.state()
+    assert [s.hist_found_inf[i] for i in range(n)] == [1, 1, 1, 0, 0, 0, 1, 0, 0, 0, 1, 0]
+    assert [s.hist_scale[i] for i in range(n)] == [h[0] for h in tr.state.history]
+    assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (tr.state.scale, tr.state.good_steps, tr.state.opt_step, tr.state.skipped_steps)
+    assert abs(float(step.loss) - tr.losses[-1]) <= 2e-3 * tr.losses[-1]
+    # the default configuration (separate inspection pass, one descriptor per tensor) takes the same decisions and bits
+    plain = St.TransformerStep(wl)
+    plain.set_batch(batch)
+    for _ in range(n):
+        plain.step()
+    assert torch.equal(plain.P.w32_arena, step.P.w32_arena) and torch.equal(plain.P.m_arena, step.P.m_arena)
+    # ... and so does the graph replay: the skip is a device-side decision inside the captured launch sequence
+    g = St.TransformerStep(wl, prechecked=True, flat_update=True, two_streams=True)
+    g.set_batch(batch)
+    g.step()
+    graph = _graph_step(g)
+    for _ in range(n - 1):
+        graph.replay()
+    torch.cuda.synchronize()
+    sg = g.state()
+    assert [sg.hist_found_inf[i] for i in range(n)] == [s.hist_found_inf[i] for i in range(n)]
+    assert torch.equal(g.P.w32_arena, step.P.w32_arena) and torch.equal(g.P.w16_arena, step.P.w16_arena)
+
+
+def test_config4_reduced_forced_overflow_in_the_prechecked_configuration():
+    """The forced overflow of config 4 (hidden row 0 x 1e4 at step 3) with the overflow inspection left to the
+    weight-gradient product's epilogue and the column sums, and one flat update descriptor."""
+    wl = I.C4_SMALL
+    step = St.XentStep(wl, prechecked=True, flat_update=True)
+    free_running(step, wl, Mo.xent_head_fwd_bwd, None, wl.steps, batch_fn=_xent_batches(wl))
+    s = step.state()
+    assert [s.hist_found_inf[i] for i in range(wl.steps)] == [int(i == wl.blowup_step) for i in range(wl.steps)]
+    plain = St.XentStep(wl)
+    bf = _xent_batches(wl)
+    for k in range(wl.steps):
+        plain.set_batch(bf(k))
+        plain.step()
+    assert torch.equal(plain.P.w32_arena, step.P.w32_arena)
+
+
+def test_config5_reduced_prechecked_configuration_matches_default():
+    wl, batch = I.C5_SMALL, I.C5_SMALL.batch()
+    a, b = St.LSTMStep(wl), St.LSTMStep(wl, prechecked=True, flat_update=True)
+    for s_ in (a, b):
+        s_.set_batch(batch)
+        for _ in range(3):
+            s_.step()
+    assert torch.equal(a.P.w32_arena, b.P.w32_arena) and a.state().opt_step == b.state().opt_step == 3
+
+
 def test_second_stream_for_weight_gradients_gives_the_same_bits():
     wl, batch = I.C3_SMALL, I.C3_SMALL.batch()
     a, b = St.TransformerStep(wl), St.TransformerStep(wl, two_streams=True)
@@ -357,8 +449,24 @@ def test_second_stream_for_weight_gradients_gives_the_same_bits():
 
 
 def test_config2_full_size():
-    wl = replace(I.C2, steps=12)
-    _transformer(wl, 2, 12)                      # growth at step 10 is inside the free run
+    """Config 2 as stated: in-situ operation checks, two teacher-forced iterations, then all 50 iterations
+    free-running against the oracle (Section 3.1 item 1: the scale is set for the NEXT iteration, so the sequence over
+    real steps is the claim): 2^15 for steps 0-9, doubling every 10 clean steps, 2^20 after the last."""
+    from test_oracle_optimizer import _golden
+    wl = I.C2
+    assert wl.steps == 50
+    f = Mo.make_transformer_fwd_bwd(wl.n_layers, wl.n_seq, wl.seq_len, wl.n_heads)
+    batch = wl.batch()
+    step = St.TransformerStep(wl)
+    step.set_batch(batch)
+    op_level_transformer(step, wl, batch)
+    teacher_forced(step, wl, f, batch, 2, grad_mode="vs_fp64")
+    run = St.TransformerStep(wl, prechecked=True, flat_update=True, two_streams=True)
+    run.set_batch(batch)
+    free_running(run, wl, f, batch, wl.steps)
+    s, g = run.state(), _golden()["c2"]
+    assert [s.hist_scale[i] for i in range(wl.steps)] == g["seq"]
+    assert (s.scale, s.good_steps, s.opt_step, s.skipped_steps) == (g["final"], g["good"], g["t"], g["skipped"])
 
 
 # ------------------------------------------------------------------ config 4
@@ -399,13 +507,6 @@ def test_config5_reduced_size():
 
 
 # ------------------------------------------------------------------ full sizes, in the configuration bench.py times
-def _graph_step(step):
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):
-        step.step()
-    return g
-
-
 def test_config3_full_size_bench_configuration():
     """Config 3 at full size exactly as bench.py launches it (producer-side overflow inspection, one flat update
     descriptor, HIP-graph replay): every operation of the first and last layer checked in situ against the oracle,
@@ -414,8 +515,8 @@ def test_config3_full_size_bench_configuration():
     batch = wl.batch()
     step = St.TransformerStep(wl, prechecked=True, flat_update=True)
     step.set_batch(batch)
-    worst = op_level_transformer(step, wl, batch, layers=(0, wl.n_layers - 1))
-    print(f"config 3 full size: worst in-situ op error {worst:.2e}")
+    worst = op_level_transformer(step, wl, batch)              # every operation of all six layers
+    print(f"config 3 full size: worst in-situ op error {worst:.2e}", flush=True)
     # the optimizer wrapper at 75.6 M parameters against the oracle on the GPU's own gradients
     before = _snapshot(step)
     s0 = step.state()
@@ -447,6 +548,21 @@ def test_config3_full_size_bench_configuration():
         assert torch.equal(two.P.w32_arena, eager.P.w32_arena) and torch.equal(two.P.w16_arena, eager.P.w16_arena)
     s = two.state()
     assert (s.opt_step, s.skipped_steps, s.scale) == (4, 0, 2.0 ** 15)
+
+
+def test_config3_full_size_three_teacher_forced_steps():
+    """Config 3 at full size in the bench configuration, three iterations against the oracle: loss, whole-network
+    gradients (as close to the fp64 definition as the oracle's, see teacher_forced), the optimizer wrapper on EVERY
+    tensor (masters and moments <= 1e-5, fp16 copies exact) and every field of the scale state."""
+    wl = I.C3
+    f = Mo.make_transformer_fwd_bwd(wl.n_layers, wl.n_seq, wl.seq_len, wl.n_heads)
+    batch = wl.batch()
+    step = St.TransformerStep(wl, prechecked=True, flat_update=True, two_streams=True)
+    step.set_batch(batch)
+    worst = teacher_forced(step, wl, f, batch, 3, grad_mode="vs_fp64", progress="config 3 full size")
+    print(f"config 3 full size, 3 teacher-forced steps: worst {worst}", flush=True)
+    s = step.state()
+    assert (s.opt_step, s.skipped_steps, s.scale, s.good_steps) == (3, 0, 2.0 ** 15, 3)
 
 
 def test_config3_full_size_scale_sequence_over_growth_interval():

@@ -105,6 +105,33 @@ def test_gemm_bwd_dx_and_dw(M, N, K):
     assert mp.scale_state_read(st).found_inf == 0
 
 
+@pytest.mark.parametrize("M,N,K", [(64, 128, 64), (300, 264, 136), (70, 90, 50)])   # matrix-core interior, ragged, scalar path
+def test_gemm_relu_epilogue_keeps_nonfinite_values(M, N, K):
+    """max(x, 0) on a non-finite pre-activation: +inf stays +inf, -inf becomes 0 and NaN stays NaN, as in the
+    oracle's definition.  A NaN that the epilogue dropped would hide a forward overflow from the gradient
+    inspection (Section 3.1 item 1)."""
+    r = RNG(M + N + K + 99)
+    x, w, b = r.standard_normal((M, K)), r.standard_normal((N, K)) * 0.1, r.standard_normal(N)
+    w[np.abs(w) < 1e-3] = 0.01                # (inf x 0 would make NaN on both sides, but keep the three cases apart)
+    x[3, 5] = np.inf                          # row 3: +-inf by the sign of w[:, 5]
+    x[7, 2] = np.nan                          # row 7: NaN everywhere
+    x[9, 1], w[4, 1] = -np.inf, 0.0           # row 9: -+inf, and NaN where the weight is zero
+    x, w, b = S16(x), S16(w), S16(b)
+    with np.errstate(invalid="ignore"):
+        ref = L.linear_fwd(MIXED, x, w, b, relu=True)
+        ref_lin = L.linear_fwd(MIXED, x, w, b)
+    assert np.isnan(ref[7]).all() and np.isnan(ref[9, 4]) and np.isposinf(ref[3]).any() and (ref[3] == 0).any()
+    y = empty16(M, N)
+    mp.mp_gemm_fwd(mp.gemm_desc(M, N, K, epilogue=2), h16(x), h16(w), h16(b), None, y)
+    got = np32(y)
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(np.isposinf(got), np.isposinf(ref))
+    assert not np.isneginf(got).any()
+    assert_close16(y, ref, 1e-3, max_ulp=1, what="relu with non-finite inputs")
+    mp.mp_gemm_fwd(mp.gemm_desc(M, N, K, epilogue=1), h16(x), h16(w), h16(b), None, y)
+    got = np32(y)
+    assert np.array_equal(np.isnan(got), np.isnan(ref_lin)) and np.array_equal(np.isneginf(got), np.isneginf(ref_lin))
+
+
 def test_gemm_dx_relu_mask_and_residual_add():
     M, N, K = 200, 136, 264
     r = RNG(7)
@@ -309,7 +336,7 @@ def test_mfma_sustained_rate_probe_reads_sanely():
     assert torch.all(sink == 0)
     r1 = mp.mp_mfma_sustained_rate(normal, sink, 256, 20000)
     assert torch.isfinite(sink).all()
-    assert 1000.0 < r1 < r0 < 2600.0, (r0, r1)
+    assert r0 > 0 and 0.3 * r0 < r1 < r0, (r0, r1)       # ratios only: absolute rates depend on the box's clocks
 
 
 @pytest.mark.parametrize("M,N,K", [(32, 4096, 2048), (32, 1024, 512), (8, 2048, 4096), (48, 520, 1000)])
@@ -477,33 +504,40 @@ def test_softmax_fwd_bwd(rows, cols):
 
 @pytest.mark.parametrize("B,H", [(32, 1024), (8, 128), (3, 50)])
 def test_lstm_cell_fwd_bwd(B, H):
+    """The cell kernels against the oracle's LSTM layer itself.  With W = [I_4H | 0] (input width 4H) and b = 0 the
+    layer's gate sums are its inputs (an exact copy), the recurrent gradient is zero and dx_t = dgates_t, so a
+    two-step sequence exposes one cell update with c_prev = 0 and one with c_prev != 0, and backward steps with and
+    without an incoming cell-state gradient."""
     r = RNG(B + H)
-    gates = S16(r.standard_normal((B, 4 * H)) * 2)
-    c_prev = (r.standard_normal((B, H))).astype(np.float32)
-    gi, gf, gg, go = (gates[:, j * H:(j + 1) * H] for j in range(4))
-    sg = lambda v: L._sigmoid(MIXED, v)
-    c_ref = sg(gf) * c_prev + sg(gi) * np.tanh(gg)
-    h_ref = MIXED.store(sg(go) * np.tanh(c_ref))
-    gd, cpd = h16(gates), f32(c_prev)
-    c, h1, h2 = empty32(B, H), empty16(B, H), torch.zeros(B, 2 * H + 8, dtype=torch.float16, device="cuda")
-    mp.mp_lstm_cell_fwd(B, H, gd, 4 * H, cpd, c, h1, H, h2[:, H:], 2 * H + 8)
-    assert np.allclose(np32(c), c_ref, rtol=2e-6, atol=2e-6)
-    assert_close16(h1, h_ref, 1e-3, max_ulp=1, what="h")
-    assert np.array_equal(bits(h2[:, H:2 * H].contiguous()), bits(h1)) and float(h2[:, :H].abs().sum()) == 0
-    # backward of the same step, checked against the oracle's formulas
-    dh_a, dh_b = S16(r.standard_normal((B, H))), S16(r.standard_normal((B, H)) * 0.3)
-    dc_in = r.standard_normal((B, H)).astype(np.float32)
-    one = np.float32(1)
-    si, sf, so, tg, tc = sg(gi), sg(gf), sg(go), np.tanh(gg), np.tanh(c_ref)
-    dh = dh_a + dh_b
-    d_o = dh * tc * so * (one - so)
-    dc = dc_in + dh * so * (one - tc * tc)
-    ref = MIXED.store(np.concatenate([dc * tg * si * (one - si), dc * c_prev * sf * (one - sf),
-                                      dc * si * (one - tg * tg), d_o], axis=1))
-    dcd, dg = f32(dc_in), empty16(B, 4 * H)
-    mp.mp_lstm_cell_bwd(B, H, gd, 4 * H, cpd, f32(c_ref), h16(dh_a), H, h16(dh_b), H, dcd, dg)
-    assert_close16(dg, ref, 1e-3, what="dgates")
-    assert np.allclose(np32(dcd), dc * sf, rtol=1e-5, atol=1e-6)
+    T = 2
+    x_seq = S16(r.standard_normal((T, B, 4 * H)) * 2)
+    w = np.concatenate([np.eye(4 * H, dtype=np.float32), np.zeros((4 * H, H), np.float32)], axis=1)
+    h_ref, cache = L.lstm_layer_fwd(MIXED, x_seq, w, np.zeros(4 * H, np.float32))
+    _, gates_all, c_all, _ = cache
+    assert np.array_equal(gates_all, x_seq)
+    gd = h16(x_seq)
+    c = [torch.zeros(B, H, dtype=torch.float32, device="cuda"), empty32(B, H), empty32(B, H)]
+    h1 = empty16(T, B, H)
+    h2 = torch.zeros(T, B, 2 * H + 8, dtype=torch.float16, device="cuda")
+    for t in range(T):
+        mp.mp_lstm_cell_fwd(B, H, gd[t], 4 * H, c[t], c[t + 1], h1[t], H, h2[t][:, H:], 2 * H + 8)
+        assert np.allclose(np32(c[t + 1]), c_all[t + 1], rtol=2e-6, atol=2e-6)
+        assert_close16(h1[t], h_ref[t], 1e-3, max_ulp=1, what=f"h[{t}]")
+        assert np.array_equal(bits(h2[t][:, H:2 * H].contiguous()), bits(h1[t])) and float(h2[t][:, :H].abs().sum()) == 0
+    # backward: dh = float(dh_a) + float(dh_b) on the device; the oracle receives that fp32 sum as the gradient from above
+    dh_a, dh_b = S16(r.standard_normal((T, B, H))), S16(r.standard_normal((T, B, H)) * 0.3)
+    dx_ref, _, _ = L.lstm_layer_bwd(MIXED, dh_a + dh_b, cache, w)      # = dgates of every step (W copies them)
+    dcd, dg = torch.zeros(B, H, dtype=torch.float32, device="cuda"), empty16(T, B, 4 * H)
+    # the device's own c would do as well; the oracle's keeps this an isolated check of the backward kernel
+    for t in (1, 0):
+        mp.mp_lstm_cell_bwd(B, H, gd[t], 4 * H, f32(c_all[t]), f32(c_all[t + 1]), h16(dh_a[t]), H, h16(dh_b[t]), H, dcd, dg[t])
+        assert_close16(dg[t], dx_ref[t], 1e-3, what=f"dgates[{t}]")
+    # one of the two addends may be absent
+    dx_ref1, _, _ = L.lstm_layer_bwd(MIXED, dh_a, cache, w)
+    dcd.zero_()
+    for t in (1, 0):
+        mp.mp_lstm_cell_bwd(B, H, gd[t], 4 * H, f32(c_all[t]), f32(c_all[t + 1]), h16(dh_a[t]), H, None, H, dcd, dg[t])
+        assert_close16(dg[t], dx_ref1[t], 1e-3, what=f"dgates[{t}] single addend")
 
 
 @pytest.mark.parametrize("rows,cols", [(4096, 512), (100, 40), (1, 8), (777, 1001), (8192, 64)])
@@ -513,6 +547,64 @@ def test_colsum(rows, cols):
     db = empty16(cols)
     mp.mp_colsum(rows, cols, h16(dy), cols, db, None, ws_bytes(mp.mp_colsum_workspace_bytes(rows, cols)))
     assert_close16(db, MIXED.store(dy.sum(0, dtype=np.float32)), 1e-3, max_ulp=1, what="colsum")
+
+
+def test_gradient_producers_flag_their_own_overflow():
+    """The column-sum and LayerNorm-backward kernels write fp16 gradients (bias, gamma, beta): when a sum leaves the
+    fp16 range the stored value is inf as in the oracle, and the overflow flag of the state they are given is set
+    (what MP_UPDATE_PRECHECKED relies on)."""
+    rows, cols = 4096, 264
+    dy = np.full((rows, cols), 2.0, np.float32)
+    dy[:, 5] = 100.0                                           # column 5 sums to 409600: beyond fp16
+    dy[:, 9] = -100.0
+    ref = MIXED.store(dy.sum(0, dtype=np.float32))
+    assert np.isposinf(ref[5]) and np.isneginf(ref[9]) and np.isfinite(np.delete(ref, [5, 9])).all()
+    st = make_state()
+    db = empty16(cols)
+    ws = ws_bytes(mp.mp_colsum_workspace_bytes(rows, cols))
+    mp.mp_colsum(rows, cols, h16(dy), cols, db, st, ws)
+    assert np.array_equal(bits(db), half_bits(ref)) and mp.scale_state_read(st).found_inf == 1
+    st = make_state()
+    mp.mp_colsum(rows, cols, h16(np.full((rows, cols), 2.0, np.float32)), cols, db, st, ws)
+    assert mp.scale_state_read(st).found_inf == 0 and torch.all(db == 8192.0)
+    # a NaN in the input reaches the sum and the flag
+    dyn = np.full((rows, cols), 1.0, np.float32)
+    dyn[77, 3] = np.nan
+    mp.mp_colsum(rows, cols, h16(dyn), cols, db, st, ws)
+    assert mp.scale_state_read(st).found_inf == 1 and np.isnan(np32(db)[3]) and np.isfinite(np.delete(np32(db), 3)).all()
+    # the weight-gradient entry point with db: flag from the bias gradient alone (dW itself stays finite)
+    d = mp.gemm_desc(rows, cols, 64)
+    x = np.zeros((rows, 64), np.float32)
+    st = make_state()
+    dw, db2 = empty16(cols, 64), empty16(cols)
+    mp.mp_gemm_bwd_dw(d, h16(dy), h16(x), dw, db2, st, ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, True)))
+    assert torch.all(dw == 0) and np.array_equal(bits(db2), half_bits(ref)) and mp.scale_state_read(st).found_inf == 1
+
+    # LayerNorm backward: dgamma = sum_rows dy xhat, dbeta = sum_rows dy, dz column sums
+    rows, d_ = 2048, 256
+    r = RNG(5)
+    x_, a_ = S16(r.standard_normal((rows, d_))), S16(r.standard_normal((rows, d_)) * 0.5)
+    gam = S16(np.ones(d_))
+    y_ref, cache = L.layernorm_fwd(MIXED, x_, a_, gam, np.zeros(d_, np.float32))
+    xd, ad, gd = h16(x_), h16(a_), h16(gam)
+    y, mean, rstd = empty16(rows, d_), empty32(rows), empty32(rows)
+    mp.mp_layernorm_fwd(rows, d_, xd, ad, gd, h16(np.zeros(d_)), L.LN_EPS, y, mean, rstd)
+    for case in ("dbeta", "dgamma", "clean"):
+        dy_ = S16(r.standard_normal((rows, d_)))
+        if case == "dbeta":
+            dy_[:, 11] = 64.0                                   # 2048 x 64 = 131072 -> inf in dbeta[11]
+        elif case == "dgamma":
+            dy_[:, 13] = S16(600.0 * np.sign(cache[0][:, 13]))  # sum |xhat| 600 ~ 1e6 -> inf in dgamma[13]
+        dz_ref, dg_ref, db_ref = L.layernorm_bwd(MIXED, dy_, cache, gam)
+        bad_ref = not (np.isfinite(dg_ref).all() and np.isfinite(db_ref).all()
+                       and np.isfinite(MIXED.store(dz_ref.sum(0, dtype=np.float32))).all())
+        assert bad_ref == (case != "clean")
+        st = make_state()
+        dz, dg, dbt, dzs = empty16(rows, d_), empty16(d_), empty16(d_), empty16(d_)
+        mp.mp_layernorm_bwd(rows, d_, h16(dy_), xd, ad, gd, mean, rstd, dz, dg, dbt, st,
+                            ws_bytes(mp.mp_layernorm_bwd_workspace_bytes(rows, d_)), dz_colsum=dzs)
+        assert mp.scale_state_read(st).found_inf == int(bad_ref), case
+        assert np.array_equal(np.isfinite(np32(dg)), np.isfinite(dg_ref)) and np.array_equal(np.isfinite(np32(dbt)), np.isfinite(db_ref))
 
 
 def test_cast_is_rne_and_overflows_to_inf():
@@ -556,11 +648,13 @@ def _run_update(ts, kind, S, t_prev, wd=0.0, poison=None, flags=0, lr=1e-3):
 
 
 @pytest.mark.parametrize("kind", ["adam", "sgd"])
-@pytest.mark.parametrize("t_prev", [0, 1, 57])
-def test_update_matches_oracle(kind, t_prev):
+@pytest.mark.parametrize("t_prev,wd", [(0, 0.0), (1, 1e-4), (57, 1e-2), (3, 0.3)])
+def test_update_matches_oracle(kind, t_prev, wd):
+    """Unscale + SGD / Adam on the masters + fp16 re-cast, with and without the fp32-side weight decay of Section 3.3
+    (g += wd * w32 after unscaling, for both optimizers)."""
     sizes = [8192 * 3 + 5, 1, 7, 4096, 100000, 33] + [64] * 40          # > 32 tensors: several launches
     ts = _tensors(RNG(20 + t_prev), sizes)
-    host, dev, ost, dst, found = _run_update(ts, kind, 2.0 ** 7, t_prev, wd=(1e-4 if kind == "sgd" else 0.0))
+    host, dev, ost, dst, found = _run_update(ts, kind, 2.0 ** 7, t_prev, wd=wd)
     assert found == 0 and dst.opt_step == ost.opt_step == t_prev + 1
     for h, d in zip(host, dev):
         assert rel_fro(np32(d["w32"]), h["w32"]) <= 1e-5

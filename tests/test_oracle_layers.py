@@ -235,3 +235,121 @@ def test_mixed_tracks_fp64_within_half_precision():
     for k in gm:
         if gm[k].ndim == 2:
             assert _rel(gm[k], g64[k]) < 4e-3, k
+
+
+# ----------------------------------------------------------------- where the fp16 roundings sit under MIXED
+class _Spy:
+    """MIXED with a record of every rounding to storage: (shape, values before rounding were all representable?)."""
+
+    def __init__(self):
+        self.log = []
+        self.name, self.acc, self.half_storage = MIXED.name, MIXED.acc, MIXED.half_storage
+
+    def island(self, x):
+        return MIXED.island(x)
+
+    def scalar(self, v):
+        return MIXED.scalar(v)
+
+    def store(self, x):
+        y = MIXED.store(x)
+        self.log.append((tuple(np.shape(x)), bool(np.array_equal(np.asarray(x, np.float32), y))))
+        return y
+
+    def shapes(self):
+        out, self.log = [s for s, _ in self.log], []
+        return out
+
+
+def _representable(x):
+    return bool(np.array_equal(MIXED.store(x), np.asarray(x, np.float32)))
+
+
+def test_mixed_storage_points_of_attention_layernorm_and_lstm():
+    """Sections 3.1 / 3.2: activations, activation gradients and weight gradients are fp16 tensors; softmax, LayerNorm
+    statistics, the loss value and the LSTM cell state are fp32 islands.  The finite-difference and autograd pins run
+    in FP64 mode, where a rounding to storage is the identity, so they cannot see a rounding that is missing or
+    misplaced under MIXED.  This pin can: it records every rounding each function performs (a dropped, added or moved
+    one changes the list) and checks that what is handed on is fp16-representable exactly where a tensor is stored and
+    is NOT where it is an fp32 island."""
+    rng = np.random.default_rng(7)
+    P = _Spy()
+    # ---- attention: scores, probabilities, context | dP, dV, dS, dQ, dK
+    B, S, H, dk = 2, 5, 3, 4
+    d = H * dk
+    qkv = MIXED.store(rng.standard_normal((B * S, 3 * d)))
+    ctx, cache = L.attention_fwd(P, qkv, B, S, H)
+    assert P.shapes() == [(B, H, S, S), (B, H, S, S), (B, H, S, dk)]
+    q, k, v, p, alpha = cache
+    assert all(_representable(t) for t in (ctx, p)) and ctx.dtype == np.float32
+    assert alpha == np.float32(0.5)                                   # 1/sqrt(dk), applied to the fp32 sum before rounding
+    dqkv = L.attention_bwd(P, MIXED.store(rng.standard_normal((B * S, d))), cache)
+    assert P.shapes() == [(B, H, S, S), (B, H, S, dk), (B, H, S, S), (B, H, S, dk), (B, H, S, dk)]
+    assert _representable(dqkv) and dqkv.shape == (B * S, 3 * d)
+    # the softmax island: probabilities are rounded once, from fp32 values that were not representable
+    P.store(L.softmax_rows(P, MIXED.store(rng.standard_normal((3, 7)))))
+    assert P.log[-1] == ((3, 7), False)
+    P.shapes()
+    # ---- LayerNorm: only y is stored forward (sum x + a, statistics, xhat stay fp32); dz, dgamma, dbeta backward
+    T = 6
+    x, a = MIXED.store(rng.standard_normal((T, d))), MIXED.store(rng.standard_normal((T, d)))
+    gam, bet = MIXED.store(1 + 0.1 * rng.standard_normal(d)), MIXED.store(0.1 * rng.standard_normal(d))
+    y, (xhat, rstd) = L.layernorm_fwd(P, x, a, gam, bet)
+    assert P.shapes() == [(T, d)]
+    assert _representable(y) and not _representable(xhat) and not _representable(rstd)
+    # the residual sum is not rounded before the statistics: x + a with a 1-ulp-of-x tail must still move the mean
+    big, tail = np.full((1, d), 2048.0, np.float32), np.zeros((1, d), np.float32)
+    tail[0, 0] = 1.0                                                  # 2049 is not an fp16 value
+    _, (xh1, _) = L.layernorm_fwd(MIXED, big, tail, np.ones(d, np.float32), np.zeros(d, np.float32))
+    assert xh1[0, 0] > 1.0                                            # rounded to 2048 it would be a constant row: xhat = 0
+    dz, dg, db = L.layernorm_bwd(P, MIXED.store(rng.standard_normal((T, d))), (xhat, rstd), gam)
+    assert P.shapes() == [(T, d), (d,), (d,)]
+    assert all(_representable(t) for t in (dz, dg, db))
+    # ---- LSTM: gates and h are stored every step, c never; backward: dgates and [dx, dh] every step, then dW, db
+    Tn, Bn, I_, Hn = 3, 2, 5, 4
+    w, b = MIXED.store(rng.standard_normal((4 * Hn, I_ + Hn)) * 0.5), MIXED.store(rng.standard_normal(4 * Hn) * 0.1)
+    h_seq, lc = L.lstm_layer_fwd(P, MIXED.store(rng.standard_normal((Tn, Bn, I_))), w, b)
+    assert P.shapes() == [(Bn, 4 * Hn), (Bn, Hn)] * Tn
+    xh_all, gates_all, c_all, _ = lc
+    assert _representable(h_seq) and _representable(gates_all) and _representable(xh_all)
+    assert all(not _representable(c) for c in c_all[1:])            # the cell state is carried in fp32
+    dx, dw, db = L.lstm_layer_bwd(P, MIXED.store(rng.standard_normal((Tn, Bn, Hn))), lc, w)
+    assert P.shapes() == [(Bn, 4 * Hn), (Bn, I_ + Hn)] * Tn + [(4 * Hn, I_ + Hn), (4 * Hn,)]
+    assert all(_representable(t) for t in (dx, dw, db))
+    # ---- linear, losses, the join of two gradient branches
+    xx, ww, bb = MIXED.store(rng.standard_normal((T, d))), MIXED.store(rng.standard_normal((7, d))), MIXED.store(rng.standard_normal(7))
+    yy = L.linear_fwd(P, xx, ww, bb, relu=True)
+    assert P.shapes() == [(T, 7)]                                     # bias and ReLU act on the fp32 sum: ONE rounding
+    L.linear_bwd(P, MIXED.store(rng.standard_normal((T, 7))), xx, ww)
+    assert P.shapes() == [(T, d), (7, d), (7,)]
+    loss, dy = L.mse_scaled(P, yy, MIXED.store(rng.standard_normal((T, 7))), 1024.0)
+    assert P.shapes() == [(T, 7)] and not _representable(loss) and _representable(dy)
+    loss, dz_ = L.softmax_xent_scaled(P, yy, rng.integers(0, 7, T), 1024.0)
+    assert P.shapes() == [(T, 7)] and _representable(dz_)
+    L.add_store(P, yy, yy)
+    assert P.shapes() == [(T, 7)]
+
+
+def test_mixed_encoder_layer_roundings_in_order():
+    """The whole encoder layer under MIXED: forward stores qkv, scores, p, ctx, attention output, y1, f, g, y2 (9);
+    backward stores, in the order of the chain rule, the three LayerNorm-2 gradients, the FFN gradients with the
+    residual join, the three LayerNorm-1 gradients, the projection gradients, the five attention gradients, the
+    fused-projection gradients and the join into dx (24)."""
+    wl = I.TransformerWorkload(index=2, n_layers=1, d_model=8, n_heads=2, d_ff=12, seq_len=4, n_seq=3)
+    P = _Spy()
+    w = {k: MIXED.store(v) for k, v in Mo.flatten_layers(wl.masters()).items()}
+    T, d, f, B, S, H = wl.tokens, 8, 12, 3, 4, 2
+    y2, c = Mo.encoder_layer_fwd(P, w, "l0.", MIXED.store(wl.batch()["x"]), B, S, H)
+    att = [(B, H, S, S), (B, H, S, S), (B, H, S, d // H)]
+    assert P.shapes() == [(T, 3 * d)] + att + [(T, d), (T, d), (T, f), (T, d), (T, d)]
+    grads = {}
+    Mo.encoder_layer_bwd(P, w, "l0.", MIXED.store(wl.batch()["target"] * 0.01), c, grads)
+    hd = (B, H, S, d // H)
+    assert P.shapes() == ([(T, d), (d,), (d,)]                       # LN2: dz2, dgamma, dbeta
+                          + [(T, f), (d, f), (d,)]                   # W2: df, dW2, db2   (the ReLU mask is a select: no rounding)
+                          + [(T, d), (f, d), (f,)] + [(T, d)]        # W1: dy1 branch, dW1, db1; join with dz2
+                          + [(T, d), (d,), (d,)]                     # LN1
+                          + [(T, d), (d, d), (d,)]                   # Wo: dctx, dWo, dbo
+                          + [(B, H, S, S), hd, (B, H, S, S), hd, hd] # attention: dP, dV, dS, dQ, dK
+                          + [(T, d), (3 * d, d), (3 * d,)] + [(T, d)])  # Wqkv: dx branch, dW, db; join with dz1
+    assert set(grads) == set(w) and all(_representable(g) for g in grads.values())
