@@ -216,6 +216,19 @@ size_t mp_colsum_workspace_bytes(int rows, int cols);
 int mp_colsum(int rows, int cols, const mp_half* dY, int ld, mp_half* db, mp_scale_state* st,
               void* ws, size_t ws_bytes, mp_stream stream);
 
+/* mp_colsum for callers that cannot allocate device memory or bring a workspace: code under HIP-graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same summation order and therefore the same
+ * bits as mp_colsum; the partial sums live in a fixed 1 MiB array inside the library's device image (one copy per
+ * GPU, held until the process ends) instead of a caller workspace.  The call allocates nothing (no hipMalloc /
+ * hipFree, no allocating library routine); the first call on a device looks the array's device address up.
+ * Limit: shapes whose mp_colsum_workspace_bytes(rows, cols) exceeds mp_colsum_static_max_bytes() (1 MiB; every
+ * shape with cols <= 262144 fits) return MP_E_WORKSPACE with nothing enqueued.  All calls on one GPU share that
+ * GPU's array: calls that may overlap in time on one GPU (different streams, different host threads) race on it
+ * and must be serialised by the caller.  Nothing in the array has to start at zero: every partial sum a call reads
+ * it has written first, so contents left by an earlier (larger) call are harmless. */
+size_t mp_colsum_static_max_bytes(void);
+int mp_colsum_static(int rows, int cols, const mp_half* dY, int ld, mp_half* db, mp_scale_state* st, mp_stream stream);
+
 /* ------------------------------------------------------------------------------------------
  * Losses: fp32 loss value (unscaled mean) and the loss-scaled fp16 seed gradient
  * (Section 3.1 item 1).  S is read from st on the device.

@@ -65,6 +65,8 @@ SIGNATURES = {
     "mp_gemm_tuning_override": (_I, [_I, _I]),
     "mp_colsum_workspace_bytes": (_SZ, [_I, _I]),
     "mp_colsum": (_I, [_I, _I, _P, _I, _P, _P, _P, _SZ, _P]),
+    "mp_colsum_static_max_bytes": (_SZ, []),
+    "mp_colsum_static": (_I, [_I, _I, _P, _I, _P, _P, _P]),
     "mp_loss_workspace_bytes": (_SZ, [_I, _I]),
     "mp_mse_scaled": (_I, [_I, _I, _P, _P, _I, _P, _P, _P, _P, _SZ, _P]),
     "mp_softmax_xent_scaled": (_I, [_I, _I, _P, _I, _P, _P, _P, _P, _P, _SZ, _P]),

@@ -135,6 +135,14 @@ def mp_colsum(rows, cols, dY, ld, db, st=None, ws=None):
                               0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 
+def mp_colsum_static_max_bytes() -> int:
+    return L.load().mp_colsum_static_max_bytes()
+
+
+def mp_colsum_static(rows, cols, dY, ld, db, st=None):
+    _check(L.load().mp_colsum_static(rows, cols, _p(dY), ld, _p(db), _p(st), _stream()))
+
+
 # ------------------------------------------------------------------ losses
 def mp_loss_workspace_bytes(rows: int, cols: int) -> int:
     return L.load().mp_loss_workspace_bytes(rows, cols)

@@ -5,6 +5,8 @@
 // two-stage through a caller workspace and deterministic.
 #include "common.hpp"
 
+#include <mutex>
+
 namespace mp {
 
 constexpr int GL_THREADS = 256;
@@ -518,21 +520,15 @@ extern "C" size_t mp_colsum_workspace_bytes(int rows, int cols) {
     return (size_t)(rb8 > rb1 ? rb8 : rb1) * cols * sizeof(float);
 }
 
-extern "C" int mp_colsum(int rows, int cols, const mp_half* dY, int ld, mp_half* db, mp_scale_state* st, void* ws,
-                         size_t ws_bytes, mp_stream stream) {
-    MP_REQUIRE(rows > 0 && cols > 0 && ld >= cols, "mp_colsum: bad shape rows=%d cols=%d ld=%d", rows, cols, ld);
-    MP_REQUIRE(dY && db, "mp_colsum: NULL argument");
-    if (!ws || ws_bytes < mp_colsum_workspace_bytes(rows, cols)) {
-        set_error("mp_colsum: workspace of %zu bytes needed, %zu given", mp_colsum_workspace_bytes(rows, cols), ws_bytes);
-        return MP_E_WORKSPACE;
-    }
+// Both launches of a column sum; `part` holds mp_colsum_workspace_bytes(rows, cols) bytes of partial sums, every one of
+// which the first launch writes before the second reads it (nothing has to start at zero).
+static int colsum_launch(int rows, int cols, const mp_half* dY, int ld, mp_half* db, mp_scale_state* st, float* part,
+                         hipStream_t hs) {
     const bool  vec = (cols % 8 == 0) && (ld % 8 == 0) && aligned16(dY);
     const int   V   = vec ? 8 : 1;
     const int   rb  = colsum_row_blocks(rows, cols, V);
     const int   rpb = (rows + rb - 1) / rb;
     const dim3  grid((cols + 8 * V - 1) / (8 * V), rb);
-    float*      part = static_cast<float*>(ws);
-    hipStream_t hs   = as_stream(stream);
     if (vec)
         hipLaunchKernelGGL(colsum_kernel<8>, grid, dim3(GL_THREADS), 0, hs, rows, cols, ld, dY, rpb, part);
     else
@@ -543,6 +539,65 @@ extern "C" int mp_colsum(int rows, int cols, const mp_half* dY, int ld, mp_half*
                        (long long)cols, cols, 1, outs, st);
     MP_LAUNCH_CHECK("mp_colsum(finish)");
     return MP_OK;
+}
+
+extern "C" int mp_colsum(int rows, int cols, const mp_half* dY, int ld, mp_half* db, mp_scale_state* st, void* ws,
+                         size_t ws_bytes, mp_stream stream) {
+    MP_REQUIRE(rows > 0 && cols > 0 && ld >= cols, "mp_colsum: bad shape rows=%d cols=%d ld=%d", rows, cols, ld);
+    MP_REQUIRE(dY && db, "mp_colsum: NULL argument");
+    if (!ws || ws_bytes < mp_colsum_workspace_bytes(rows, cols)) {
+        set_error("mp_colsum: workspace of %zu bytes needed, %zu given", mp_colsum_workspace_bytes(rows, cols), ws_bytes);
+        return MP_E_WORKSPACE;
+    }
+    return colsum_launch(rows, cols, dY, ld, db, st, static_cast<float*>(ws), as_stream(stream));
+}
+
+// ---- column sums for callers that cannot allocate (code under HIP-graph capture, serving loops, harnesses that
+// forbid hipMalloc): the partial sums live in a fixed array in the library's device image instead of a caller
+// workspace.  Every GPU holds its own copy of the array at its own address; the array's NAME is only a host-side
+// handle, so the device address is looked up once per device and only that pointer is ever handed to a kernel.
+constexpr size_t kColsumScratchFloats = 262144;  // 1 MiB: covers every shape with cols <= 262144 (see the row-block rule)
+static __device__ __align__(256) float scratch[kColsumScratchFloats];
+
+constexpr int     kMaxDevices = 64;
+static float*     g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, once looked up
+static std::mutex g_scratch_mu;
+
+static int colsum_scratch(float** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "mp_colsum_static: hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("mp_colsum_static: device index %d outside 0..%d", dev, kMaxDevices - 1);
+        return MP_E_UNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // for the CURRENT device, which is `dev`
+        if (e != hipSuccess || p == nullptr) return hip_fail(e, "mp_colsum_static: hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = static_cast<float*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return MP_OK;
+}
+
+extern "C" size_t mp_colsum_static_max_bytes(void) { return kColsumScratchFloats * sizeof(float); }
+
+extern "C" int mp_colsum_static(int rows, int cols, const mp_half* dY, int ld, mp_half* db, mp_scale_state* st,
+                                mp_stream stream) {
+    MP_REQUIRE(rows > 0 && cols > 0 && ld >= cols, "mp_colsum_static: bad shape rows=%d cols=%d ld=%d", rows, cols, ld);
+    MP_REQUIRE(dY && db, "mp_colsum_static: NULL argument");
+    const size_t need = mp_colsum_workspace_bytes(rows, cols);
+    if (need > kColsumScratchFloats * sizeof(float)) {
+        set_error("mp_colsum_static: %d x %d needs %zu bytes of partial sums, the built-in scratch holds %zu; use mp_colsum "
+                  "with a workspace", rows, cols, need, kColsumScratchFloats * sizeof(float));
+        return MP_E_WORKSPACE;
+    }
+    float* part = nullptr;
+    const int rc = colsum_scratch(&part);
+    if (rc != MP_OK) return rc;
+    return colsum_launch(rows, cols, dY, ld, db, st, part, as_stream(stream));
 }
 
 // ---- LayerNorm
