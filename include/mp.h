@@ -7,10 +7,10 @@
  * regularisation on the fp32 copy):
  *
  *   forward  : mp_gemm_fwd[_ws] (+ mp_layernorm_fwd, mp_attention_fwd | mp_softmax_fwd,
- *              mp_lstm_cell_fwd)
+ *              mp_lstm_cell_fwd | mp_lstm_layer_fwd)
  *   loss     : mp_mse_scaled | mp_softmax_xent_scaled      (seed gradient x loss scale)
  *   backward : mp_gemm_bwd_dx[_ws], mp_gemm_bwd_dw | mp_gemm_bwd_dw_grouped (+ mp_layernorm_bwd,
- *              mp_attention_bwd | mp_softmax_bwd, mp_lstm_cell_bwd, mp_colsum)
+ *              mp_attention_bwd | mp_softmax_bwd, mp_lstm_cell_bwd | mp_lstm_layer_bwd, mp_colsum)
  *   update   : mp_unscale_check_update   (inspect fp16 gradients, unscale, SGD/Adam on
  *                                         fp32 masters, rewrite the fp16 copies - or skip)
  *              mp_loss_scale_update      (halve / count / grow the loss scale)
@@ -311,6 +311,53 @@ int mp_lstm_cell_fwd(int B, int H, const mp_half* gates, int ldg, const float* c
 int mp_lstm_cell_bwd(int B, int H, const mp_half* gates, int ldg, const float* c_prev, const float* c,
                      const mp_half* dh_a, int ld_a, const mp_half* dh_b, int ld_b, float* dc,
                      mp_half* dgates, mp_stream stream);
+
+/* A whole LSTM layer over all time steps in ONE launch per direction (the recurrent encoder of the Section 2 listing
+ * and Section 5.1; arithmetic of Sections 3.1 / 3.2 as in the per-step calls: fp16 operands, fp32 sums, each gate sum
+ * and each h_t rounded once to fp16, cell state fp32).  Unrolled step by step a layer is a chain of small dependent
+ * launches; here every workgroup keeps its rows of the recurrent weights on chip for all T steps and the steps are
+ * separated by a grid-wide barrier inside the kernel.
+ *
+ *   forward : gates_t = RNE16( gx_t + h_{t-1} W_h^T + b ),   W_h = columns [I, I+H) of w[4H, ldw], gate blocks (i, f, g, o)
+ *             c_t = sigma(f) c_{t-1} + sigma(i) tanh(g)  (fp32),   h_t = RNE16( sigma(o) tanh(c_t) )
+ *     gx     device fp32 [T*B, 4H] (ld 4H): the input half x_t W_x^T of every step's gate sums, e.g. from ONE
+ *            mp_gemm_fwd with y_f32 over all T*B rows; kept fp32 so the gate sum is still rounded once.
+ *     gates  device fp16 [T*B, 4H] out (kept for the backward pass).
+ *     c      device fp32 [(T+1)*B, H]: rows [0, B) hold c_0 on entry, rows of steps 1..T are written.
+ *     xh     device fp16 [T*B, ldxh]: columns [I, I+H) of step 0 hold h_0 on entry; h_t is written into the same
+ *            columns of step t+1 (t+1 < T).  Columns [0, I) are not touched (they hold x_t for the weight gradient).
+ *     h_up   device fp16 [T*B, ld_up] or NULL: h_t is also written to columns [0, H) of row block t (the next layer's
+ *            input, or the output).
+ *   backward: per step t = T-1 .. 0, dh = float(dh_above_t) + float(dh_rec),
+ *             dgates_t = RNE16(cell backward, see mp_lstm_cell_bwd),  dh_rec = RNE16( dgates_t W_h )  for step t-1.
+ *     dh_above device fp16 [T*B, ld_up]: gradient reaching h_t from above (leading dimension d->ld_up).
+ *     dgates   device fp16 [T*B, 4H] out.  The input gradient dgates W_x and the weight / bias gradients are ordinary
+ *              large products over all T*B rows afterwards (mp_gemm_bwd_dx, mp_gemm_bwd_dw).
+ *   status   device int32, must be 0 on entry (the caller clears it; it is never cleared here).  The kernel's step
+ *            barrier waits at most wait_limit_us (0: 2 s) for the other workgroups; a wait that runs out sets
+ *            *status nonzero, every workgroup then leaves its loop, and the outputs are undefined.  A nonzero status
+ *            on entry makes the kernel stop at its first barrier.  Check it wherever the host next synchronises.
+ *   ws       device, mp_lstm_layer_workspace_bytes() bytes, 4-byte aligned (step flags; cleared by the call).
+ * All H / 16 workgroups must be resident at once: the call returns MP_E_UNSUPPORTED if the device has fewer compute
+ * units, and launches of this kind that may run at the same time (other streams) must together fit the device.
+ * Supported: B <= 32, H a multiple of 128 up to 1024, I, ldw, ldxh multiples of 8, ld_up even, 16-byte aligned
+ * pointers; otherwise MP_E_UNSUPPORTED (run the layer with mp_gemm_fwd_ws / mp_lstm_cell_fwd step by step).
+ * debug_extra_participants (0 in production) makes the barrier wait for that many flags nobody raises: with a small
+ * wait_limit_us it lets a test drive the time-out path while every wave still exits normally. */
+typedef struct mp_lstm_layer_desc {
+    int32_t T, B, I, H;       /* time steps, batch rows, input width, hidden units                         */
+    int32_t ldw, ldxh, ld_up; /* leading dimensions of w, xh, and of h_up (forward) / dh_above (backward)   */
+    int32_t wait_limit_us;    /* bound of one barrier wait; 0 = 2 000 000                                   */
+    int32_t debug_extra_participants;
+    int32_t reserved;
+} mp_lstm_layer_desc;
+size_t mp_lstm_layer_workspace_bytes(void);
+int mp_lstm_layer_fwd(const mp_lstm_layer_desc* d /* host */, const float* gx, const mp_half* w, const mp_half* bias,
+                      mp_half* gates, float* c, mp_half* xh, mp_half* h_up, int32_t* status, void* ws, size_t ws_bytes,
+                      mp_stream stream);
+int mp_lstm_layer_bwd(const mp_lstm_layer_desc* d /* host */, const mp_half* w, const mp_half* gates, const float* c,
+                      const mp_half* dh_above, mp_half* dgates, int32_t* status, void* ws, size_t ws_bytes,
+                      mp_stream stream);
 
 /* dst = RNE16(src), n elements (initial fp16 copies of masters and inputs). */
 int mp_cast_f32_to_f16(size_t n, const float* src, mp_half* dst, mp_stream stream);

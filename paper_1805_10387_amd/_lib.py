@@ -36,6 +36,12 @@ class GemmGroupItem(C.Structure):
     _fields_ = [("desc", GemmDesc), ("dY", C.c_void_p), ("X", C.c_void_p), ("dW", C.c_void_p)]
 
 
+class LstmLayerDesc(C.Structure):
+    _fields_ = [("T", C.c_int32), ("B", C.c_int32), ("I", C.c_int32), ("H", C.c_int32),
+                ("ldw", C.c_int32), ("ldxh", C.c_int32), ("ld_up", C.c_int32), ("wait_limit_us", C.c_int32),
+                ("debug_extra_participants", C.c_int32), ("reserved", C.c_int32)]
+
+
 class TensorDesc(C.Structure):
     _fields_ = [("g16", C.c_void_p), ("w32", C.c_void_p), ("w16", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("n", C.c_size_t)]
@@ -79,6 +85,9 @@ SIGNATURES = {
     "mp_attention_bwd": (_I, [_I, _I, _I, _I, _P, _I, _F, _P, _P, _I, _P, _I, _P]),
     "mp_lstm_cell_fwd": (_I, [_I, _I, _P, _I, _P, _P, _P, _I, _P, _I, _P]),
     "mp_lstm_cell_bwd": (_I, [_I, _I, _P, _I, _P, _P, _P, _I, _P, _I, _P, _P, _P]),
+    "mp_lstm_layer_workspace_bytes": (_SZ, []),
+    "mp_lstm_layer_fwd": (_I, [C.POINTER(LstmLayerDesc), _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mp_lstm_layer_bwd": (_I, [C.POINTER(LstmLayerDesc), _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "mp_cast_f32_to_f16": (_I, [_SZ, _P, _P, _P]),
     "mp_fill_u32": (_I, [_SZ, C.c_uint32, _P, _P]),
     "mp_mfma_sustained_rate": (_I, [_P, _SZ, _P, _SZ, _I, _I, C.POINTER(C.c_double), _P]),

@@ -198,6 +198,24 @@ def mp_lstm_cell_bwd(B, H, gates, ldg, c_prev, c, dh_a, ld_a, dh_b, ld_b, dc, dg
                                      _p(dgates), _stream()))
 
 
+def lstm_layer_desc(T, B, I, H, ldw, ldxh, ld_up, wait_limit_us=0, debug_extra_participants=0) -> L.LstmLayerDesc:
+    return L.LstmLayerDesc(T, B, I, H, ldw, ldxh, ld_up, wait_limit_us, debug_extra_participants, 0)
+
+
+def mp_lstm_layer_workspace_bytes() -> int:
+    return L.load().mp_lstm_layer_workspace_bytes()
+
+
+def mp_lstm_layer_fwd(desc, gx, w, bias, gates, c, xh, h_up, status, ws):
+    _check(L.load().mp_lstm_layer_fwd(C.byref(desc), _p(gx), _p(w), _p(bias), _p(gates), _p(c), _p(xh), _p(h_up), _p(status),
+                                      _p(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def mp_lstm_layer_bwd(desc, w, gates, c, dh_above, dgates, status, ws):
+    _check(L.load().mp_lstm_layer_bwd(C.byref(desc), _p(w), _p(gates), _p(c), _p(dh_above), _p(dgates), _p(status), _p(ws),
+                                      ws.numel() * ws.element_size(), _stream()))
+
+
 def mp_cast_f32_to_f16(n, src, dst):
     _check(L.load().mp_cast_f32_to_f16(n, _p(src), _p(dst), _stream()))
 

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmp.so")
-SOURCES = ["gemm_kk.hip", "gemm_ko.hip", "gemm_oo.hip", "gemm.hip", "update.hip", "loss.hip", "glue.hip", "attention.hip", "probe.hip"]
+SOURCES = ["gemm_kk.hip", "gemm_ko.hip", "gemm_oo.hip", "gemm.hip", "update.hip", "loss.hip", "glue.hip", "attention.hip", "lstm.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,

@@ -3,6 +3,7 @@
 // (paper Sections 3.1, 3.2).  Every kernel reads each stored input once and writes each stored
 // output once; row reductions are wave-level (one 64-lane wave per row), column reductions are
 // two-stage through a caller workspace and deterministic.
+#include "cell_math.hpp"
 #include "common.hpp"
 
 #include <mutex>
@@ -420,8 +421,6 @@ __global__ __launch_bounds__(GL_THREADS) void softmax_bwd_generic_kernel(long lo
 }
 
 // --------------------------------------------------------------------------- LSTM cell
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + __expf(-x)); }
-
 __global__ __launch_bounds__(GL_THREADS) void lstm_cell_fwd_kernel(int B, int H, const uint16_t* __restrict__ gates,
                                                                    int ldg, const float* __restrict__ c_prev,
                                                                    float* __restrict__ c, uint16_t* __restrict__ h1,
@@ -430,10 +429,8 @@ __global__ __launch_bounds__(GL_THREADS) void lstm_cell_fwd_kernel(int B, int H,
     if (idx >= B * H) return;
     const int       b = idx / H, j = idx - b * H;
     const uint16_t* g  = gates + (long long)b * ldg;
-    const float     gi = h2f(g[j]), gf = h2f(g[H + j]), gg = h2f(g[2 * H + j]), go = h2f(g[3 * H + j]);
-    const float     cn = sigmoidf_(gf) * c_prev[idx] + sigmoidf_(gi) * tanhf(gg);
-    c[idx]             = cn;
-    const uint16_t hv  = f2h(sigmoidf_(go) * tanhf(cn));
+    uint16_t        hv;
+    c[idx] = lstm_cell_forward(h2f(g[j]), h2f(g[H + j]), h2f(g[2 * H + j]), h2f(g[3 * H + j]), c_prev[idx], &hv);
     h1[(long long)b * ldh + j] = hv;
     if (h2 != nullptr) h2[(long long)b * ldh2 + j] = hv;
 }
@@ -450,22 +447,16 @@ __global__ __launch_bounds__(GL_THREADS) void lstm_cell_bwd_kernel(int B, int H,
     const int       b = idx / H, j = idx - b * H;
     const uint16_t* g  = gates + (long long)b * ldg;
     uint16_t*       dg = dgates + (long long)b * ldg;
-    const float     si = sigmoidf_(h2f(g[j])), sf = sigmoidf_(h2f(g[H + j]));
-    const float     tg = tanhf(h2f(g[2 * H + j])), so = sigmoidf_(h2f(g[3 * H + j]));
-    const float     tc = tanhf(c[idx]);
     float           dh = 0.f;
     if (dh_a != nullptr) dh += h2f(dh_a[(long long)b * ld_a + j]);
     if (dh_b != nullptr) dh += h2f(dh_b[(long long)b * ld_b + j]);
-    const float d_o = dh * tc * so * (1.0f - so);
-    const float dc  = dc_io[idx] + dh * so * (1.0f - tc * tc);
-    const float d_i = dc * tg * si * (1.0f - si);
-    const float d_f = dc * c_prev[idx] * sf * (1.0f - sf);
-    const float d_g = dc * si * (1.0f - tg * tg);
-    dc_io[idx]      = dc * sf;
-    dg[j]           = f2h(d_i);
-    dg[H + j]       = f2h(d_f);
-    dg[2 * H + j]   = f2h(d_g);
-    dg[3 * H + j]   = f2h(d_o);
+    uint16_t d4[4];
+    dc_io[idx] = lstm_cell_backward(h2f(g[j]), h2f(g[H + j]), h2f(g[2 * H + j]), h2f(g[3 * H + j]), c_prev[idx], c[idx], dh,
+                                    dc_io[idx], d4);
+    dg[j]         = d4[0];
+    dg[H + j]     = d4[1];
+    dg[2 * H + j] = d4[2];
+    dg[3 * H + j] = d4[3];
 }
 
 // --------------------------------------------------------------------------- cast / fill

@@ -352,11 +352,16 @@ class XentStep(_StepBase):
 class LSTMStep(_StepBase):
     """Stacked LSTM unrolled over time with an MSE loss on the top layer's outputs (config 5).
 
-    Layer l keeps xh[l][t] = [input_t | h_{t-1}] as one row block so the gate contraction is a single
-    product with W[4H, I+H]; the cell kernel writes h_t both into xh[l][t+1] (recurrence) and into
-    the next layer's xh[l+1][t] (or the output)."""
+    Layer l keeps xh[l][t] = [input_t | h_{t-1}] as one row block.  Two launch plans give the same stored tensors:
 
-    def __init__(self, wl, masters=None, **kw):
+    persistent (default where the shape allows): per layer ONE large product for the input half of all gate sums
+      (fp32, x W_x^T over all T*B rows), then ONE recurrent kernel that runs all T steps with the recurrent weights
+      on chip (mp_lstm_layer_fwd); backward likewise one recurrent kernel per layer (mp_lstm_layer_bwd) followed by
+      the large input-gradient and weight-gradient products over all T*B rows.
+    step by step: per time step one gate product with W[4H, I+H] (mp_gemm_fwd_ws) and one cell kernel; the cell
+      kernel writes h_t both into xh[l][t+1] (recurrence) and into the next layer's xh[l+1][t] (or the output)."""
+
+    def __init__(self, wl, masters=None, persistent=True, **kw):
         if masters is None:
             masters = {f"l{i}.{k}": v for i, lay in enumerate(wl.masters()) for k, v in lay.items()}
         super().__init__(masters, wl.opt, wl.scale, **kw)
@@ -365,6 +370,8 @@ class LSTMStep(_StepBase):
         z16 = lambda *s: torch.zeros(s, dtype=torch.float16, device="cuda")
         z32 = lambda *s: torch.zeros(s, dtype=torch.float32, device="cuda")
         self.in_dims = [wl.d_in if l == 0 else H for l in range(NL)]
+        self.persistent = (persistent and Bt <= 32 and H % 128 == 0 and H <= 1024 and all(i % 8 == 0 for i in self.in_dims)
+                           and H // 16 <= torch.cuda.get_device_properties(0).multi_processor_count)
         self.xh = [z16(T, Bt, self.in_dims[l] + H) for l in range(NL)]      # h_0 = 0 stays in xh[l][0][:, I:]
         self.gates = [z16(T, Bt, 4 * H) for _ in range(NL)]
         self.c = [z32(T + 1, Bt, H) for _ in range(NL)]                      # c_0 = 0
@@ -380,6 +387,16 @@ class LSTMStep(_StepBase):
         # the recurrent products have only `batch` rows: with a workspace they split their contraction over the chip
         need += [B.mp_gemm_split_workspace_bytes(x) for x in self.d_gate]
         self._alloc_ws(max(need))
+        if self.persistent:
+            self.gx = z32(T * Bt, 4 * H)                                     # input half of the gate sums, all steps
+            self.dx = [z16(T * Bt, max(self.in_dims)) for _ in range(2)]     # input gradient of a layer, all steps
+            self.rl_status = torch.zeros(1, dtype=torch.int32, device="cuda")
+            self.rl_ws = torch.zeros(B.mp_lstm_layer_workspace_bytes() // 4, dtype=torch.int32, device="cuda")
+            # x W_x^T and dgates W_x: the input columns [0, I) of W[4H, I+H], all T*B rows at once
+            self.d_in_all = [B.gemm_desc(T * Bt, 4 * H, self.in_dims[l], ldx=self.in_dims[l] + H, ldw=self.in_dims[l] + H)
+                             for l in range(NL)]
+            self.d_dx_all = [B.gemm_desc(T * Bt, 4 * H, self.in_dims[l], ldx=self.in_dims[l], ldw=self.in_dims[l] + H)
+                             for l in range(NL)]
 
     def set_batch(self, batch):
         x = _h16(batch["x"])
@@ -387,6 +404,38 @@ class LSTMStep(_StepBase):
         self.target.copy_(_h16(batch["target"]))
 
     def forward_backward(self):
+        if self.persistent:
+            self._forward_backward_persistent()
+        else:
+            self._forward_backward_stepwise()
+
+    def recurrent_kernels_ok(self) -> bool:
+        """False if a step barrier of a persistent kernel ever ran out of time (synchronises; tests and logging)."""
+        return (not self.persistent) or int(self.rl_status.item()) == 0
+
+    def _forward_backward_persistent(self):
+        wl, w, g = self.wl, self.P.w16, self.P.g16
+        T, Bt, H, NL = wl.seq_len, wl.batch_size, wl.hidden, wl.n_layers
+        for l in range(NL):
+            I = self.in_dims[l]
+            B.mp_gemm_fwd(self.d_in_all[l], self.xh[l], w[f"l{l}.w"], None, None, None, self.gx)
+            up, ldup = (self.xh[l + 1], self.in_dims[l + 1] + H) if l + 1 < NL else (self.y, H)
+            d = B.lstm_layer_desc(T, Bt, I, H, I + H, I + H, ldup)
+            B.mp_lstm_layer_fwd(d, self.gx, w[f"l{l}.w"], w[f"l{l}.b"], self.gates[l], self.c[l], self.xh[l], up,
+                                self.rl_status, self.rl_ws)
+        B.mp_mse_scaled(T * Bt, H, self.y, self.target, H, self.st, self.loss, self.dy, self.ws)
+        above, ld_above = self.dy, H
+        for l in range(NL - 1, -1, -1):
+            I = self.in_dims[l]
+            d = B.lstm_layer_desc(T, Bt, I, H, I + H, I + H, ld_above)
+            B.mp_lstm_layer_bwd(d, w[f"l{l}.w"], self.gates[l], self.c[l], above, self.dgates, self.rl_status, self.rl_ws)
+            dx = self.dx[l % 2].view(-1)[:T * Bt * I].view(T * Bt, I)
+            B.mp_gemm_bwd_dx(self.d_dx_all[l], self.dgates, w[f"l{l}.w"], dx)
+            B.mp_gemm_bwd_dw(self.d_gate_all[l], self.dgates, self.xh[l], g[f"l{l}.w"], g[f"l{l}.b"], self.st_grad, self.ws)
+            above, ld_above = dx, I
+        self.dx_input = above
+
+    def _forward_backward_stepwise(self):
         wl, w, g = self.wl, self.P.w16, self.P.g16
         T, Bt, H, NL = wl.seq_len, wl.batch_size, wl.hidden, wl.n_layers
         for l in range(NL):

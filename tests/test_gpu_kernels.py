@@ -540,6 +540,92 @@ def test_lstm_cell_fwd_bwd(B, H):
         assert_close16(dg[t], dx_ref1[t], 1e-3, what=f"dgates[{t}] single addend")
 
 
+def _persistent_lstm_layer(T, Bn, I, H, x_seq, w, b, dh_seq, wait_limit_us=0, extra=0):
+    """One LSTM layer through the persistent kernels: input half of the gate sums as one fp32 product, the recurrent
+    kernel, and (backward) the recurrent kernel followed by the large input-gradient and weight-gradient products."""
+    ld = I + H
+    xh = torch.zeros(T, Bn, ld, dtype=torch.float16, device="cuda")
+    xh[:, :, :I].copy_(h16(x_seq))
+    wd, bd = h16(w), h16(b)
+    gx = empty32(T * Bn, 4 * H)
+    mp.mp_gemm_fwd(mp.gemm_desc(T * Bn, 4 * H, I, ldx=ld, ldw=ld), xh, wd, None, None, None, gx)
+    gates, c = empty16(T, Bn, 4 * H), torch.zeros(T + 1, Bn, H, dtype=torch.float32, device="cuda")
+    h_up = torch.full((T, Bn, H + 2), 5.0, dtype=torch.float16, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(mp.mp_lstm_layer_workspace_bytes() // 4, dtype=torch.int32, device="cuda")
+    d = mp.lstm_layer_desc(T, Bn, I, H, ld, ld, H + 2, wait_limit_us, extra)
+    mp.mp_lstm_layer_fwd(d, gx, wd, bd, gates, c, xh, h_up, status, ws)
+    out = dict(xh=xh, gates=gates, c=c, h_up=h_up, status=status)
+    if dh_seq is not None:
+        dgates = empty16(T, Bn, 4 * H)
+        mp.mp_lstm_layer_bwd(mp.lstm_layer_desc(T, Bn, I, H, ld, ld, H, wait_limit_us, extra), wd, gates, c, h16(dh_seq), dgates, status, ws)
+        dx, dw, db = empty16(T * Bn, max(I, 8)), empty16(4 * H, ld), empty16(4 * H)
+        if I > 0:
+            dx = empty16(T * Bn, I)
+            mp.mp_gemm_bwd_dx(mp.gemm_desc(T * Bn, 4 * H, I, ldx=I, ldw=ld), dgates, wd, dx)
+        dall = mp.gemm_desc(T * Bn, 4 * H, ld)
+        mp.mp_gemm_bwd_dw(dall, dgates, xh, dw, db, None, ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(dall, True)))
+        out.update(dgates=dgates, dx=dx, dw=dw, db=db)
+    return out
+
+
+@pytest.mark.parametrize("T,Bn,I,H", [(6, 8, 96, 128), (5, 20, 64, 256), (3, 32, 8, 384), (4, 1, 0, 128), (10, 32, 1024, 1024)])
+def test_lstm_persistent_layer_kernels(T, Bn, I, H):
+    """All time steps of a layer in one launch per direction against the oracle's layer functions: every stored tensor
+    of the forward pass (gate sums, h_t, fp32 cell states) and, from the GPU's own forward tensors, the gradients.
+    Shapes: one and several workgroups, batch rows below / between / at the 16-row matrix-core blocks, no input half
+    at all (I = 0), and config 5's layer at full width."""
+    r = RNG(T * 1000 + Bn + I + H)
+    x_seq = S16(r.standard_normal((T, Bn, I)))
+    w, b = S16(r.uniform(-0.1, 0.1, (4 * H, I + H))), S16(r.standard_normal(4 * H) * 0.1)
+    dh_seq = S16(r.standard_normal((T, Bn, H)))
+    h_ref, cache = L.lstm_layer_fwd(MIXED, x_seq, w, b)
+    xh_ref, gates_ref, c_ref, _ = cache
+    o = _persistent_lstm_layer(T, Bn, I, H, x_seq, w, b, dh_seq)
+    assert int(o["status"].item()) == 0
+    assert_close16(o["gates"][0], gates_ref[0], 1e-3, max_ulp=1, what="gate sums of step 0")   # same inputs on both sides
+    assert_close16(o["gates"], gates_ref, 1e-3, what="gate sums")      # later steps see the device's own h_{t-1}
+    assert_close16(o["h_up"][:, :, :H], h_ref, 1e-3, what="h")
+    assert torch.all(o["h_up"][:, :, H:] == 5.0)
+    assert_close16(o["xh"], xh_ref, 1e-3, what="[x, h_prev] row blocks")
+    assert rel_fro(np32(o["c"]), np.stack(c_ref)) <= 1e-3
+    # backward from the device's own stored forward tensors (what a training step differentiates)
+    cache_gpu = (np32(o["xh"]), np32(o["gates"]), list(np32(o["c"])), I)
+    dx_ref, dw_ref, db_ref = L.lstm_layer_bwd(MIXED, dh_seq, cache_gpu, w)
+    if I > 0:
+        assert_close16(o["dx"].view(T, Bn, I), dx_ref, 1e-3, what="dx")
+    assert_close16(o["dw"], dw_ref, 1e-3, what="dW")
+    assert_close16(o["db"], db_ref, 1e-3, what="db")
+
+
+def test_lstm_persistent_layer_timeout_path_and_rejections():
+    """The step barrier's wait is bounded: asked to wait for a flag nobody raises (debug_extra_participants) with a
+    2 ms limit, every workgroup gives up, the kernels end normally and *status reports it; a poisoned status makes the
+    next launch stop at its first barrier; after clearing it the same buffers give the right answer again."""
+    T, Bn, I, H = 4, 8, 32, 256
+    r = RNG(77)
+    x_seq, w, b = S16(r.standard_normal((T, Bn, I))), S16(r.uniform(-0.1, 0.1, (4 * H, I + H))), S16(np.zeros(4 * H))
+    o = _persistent_lstm_layer(T, Bn, I, H, x_seq, w, b, S16(r.standard_normal((T, Bn, H))), wait_limit_us=2000, extra=1)
+    torch.cuda.synchronize()
+    assert int(o["status"].item()) != 0
+    h_ref, _ = L.lstm_layer_fwd(MIXED, x_seq, w, b)
+    good = _persistent_lstm_layer(T, Bn, I, H, x_seq, w, b, None)
+    assert int(good["status"].item()) == 0
+    assert_close16(good["h_up"][:, :, :H], h_ref, 1e-3, what="h after a timed-out launch")
+    # unsupported shapes are refused before anything is launched
+    ws = torch.zeros(mp.mp_lstm_layer_workspace_bytes() // 4, dtype=torch.int32, device="cuda")
+    st = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for (Bx, Hx, Ix) in ((33, 128, 8), (8, 192, 8), (8, 2048, 8), (8, 128, 4)):
+        with pytest.raises(mp.MPError) as e:
+            mp.mp_lstm_layer_fwd(mp.lstm_layer_desc(2, Bx, Ix, Hx, Ix + Hx, Ix + Hx, Hx), empty32(2 * Bx, 4 * Hx), empty16(4 * Hx, Ix + Hx),
+                                 empty16(4 * Hx), empty16(2, Bx, 4 * Hx), empty32(3, Bx, Hx), empty16(2, Bx, Ix + Hx), None, st, ws)
+        assert e.value.code == ML.MP_E_UNSUPPORTED
+    with pytest.raises(mp.MPError) as e:
+        mp.mp_lstm_layer_fwd(mp.lstm_layer_desc(2, 8, 8, 128, 136, 136, 128), empty32(16, 512), empty16(512, 136), empty16(512),
+                             empty16(2, 8, 512), empty32(3, 8, 128), empty16(2, 8, 136), None, None, ws)
+    assert e.value.code == ML.MP_E_INVAL
+
+
 @pytest.mark.parametrize("rows,cols", [(4096, 512), (100, 40), (1, 8), (777, 1001), (8192, 64)])
 def test_colsum(rows, cols):
     r = RNG(rows + cols)
