@@ -3,8 +3,9 @@
 // operands, fp32 sums, fp16 storage points, fp32 cell state).
 //
 // A layer unrolled over time is a chain of small dependent products (batch rows x [4H, H]): launched one by one a time
-// step costs its launches and first-load latencies, not its bytes.  Here each workgroup owns RL_UNITS hidden units for
-// the whole sequence:
+// step costs its launches and first-load latencies, not its bytes.  Here each workgroup owns RL_UNITS hidden units of
+// RL_ROWS batch rows for the whole sequence (batch rows never mix in the recurrence, so each block of rows is a grid
+// of its own with its own step barrier):
 //   forward : its 4 x RL_UNITS rows of the recurrent weight block W_h live in registers as matrix-core fragments for
 //             all T steps; per step it reads h_{t-1} (all units, B x H fp16) from memory, forms its gate sums, adds
 //             the input half x_t W_x^T (computed for all steps at once by one large product beforehand, kept fp32, so
@@ -25,7 +26,9 @@ namespace mp {
 
 constexpr int RL_THREADS = 256;  // 4 waves: each takes a quarter of the contraction
 constexpr int RL_UNITS   = 16;   // hidden units per workgroup = one 16-row matrix-core block per gate
+constexpr int RL_ROWS    = 16;   // batch rows per workgroup = one matrix-core block; more rows: more workgroups (grid y)
 constexpr int RL_MAX_H   = 1024; // register budget of the fragment arrays below
+constexpr int RL_FLAG_WORDS = 128;  // flag words per barrier group (one group per block of batch rows)
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
@@ -36,35 +39,43 @@ struct RlSync {
     long long limit_ticks;  // bound of one wait, in ticks of the constant 100 MHz clock
 };
 
-// All of this workgroup's global stores of the step become visible device-wide, then its flag is raised.
+// This workgroup has finished `step`: its flag is raised once all its global stores of the step are visible
+// device-wide.  The workgroup barrier waits until every wave's stores have left the compute unit and orders them
+// before thread 0, whose device-scope release store then publishes them (one write-back of the cache level that
+// other compute-unit clusters cannot see, per workgroup and step, instead of one per wave).
 __device__ __forceinline__ void grid_arrive(const RlSync& s, int step) {
-    __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) __hip_atomic_store(s.flags + blockIdx.x, step, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Wait until every flag has reached `step`.  Returns false (for the whole workgroup alike) when the wait was
-// abandoned: its time ran out, or another workgroup had already given up.
-__device__ __forceinline__ bool grid_wait(const RlSync& s, int step) {
-    const long long t0 = wall_clock64();
-    bool            ok = true;
-    for (;;) {
-        int mine = 1;
-        for (int i = threadIdx.x; i < s.nwait; i += RL_THREADS)
-            mine &= __hip_atomic_load(s.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= step;
-        if (__syncthreads_and(mine)) break;
-        int give_up = 0;
-        if (threadIdx.x == 0)
-            give_up = (wall_clock64() - t0 > s.limit_ticks) ||
-                      __hip_atomic_load(s.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
-        if (__syncthreads_or(give_up)) {
-            ok = false;
-            break;
+// abandoned: its time ran out, or another workgroup had already given up.  Wave 0 polls (lane i watches flags i,
+// i + 64, ...), takes the device-scope acquire, and hands the verdict to the other waves through `verdict` (LDS)
+// and a workgroup barrier, which orders everything they read afterwards behind that acquire.
+__device__ __forceinline__ bool grid_wait(const RlSync& s, int step, int* verdict) {
+    if (threadIdx.x < 64) {
+        const long long t0 = wall_clock64();
+        int             ok = 1;
+        for (;;) {
+            int mine = 1;
+            for (int i = threadIdx.x; i < s.nwait; i += 64)
+                mine &= __hip_atomic_load(s.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= step;
+            if (__all(mine)) break;
+            const int give_up = (wall_clock64() - t0 > s.limit_ticks) ||
+                                __hip_atomic_load(s.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+            if (__any(give_up)) {  // (lanes read the clock a few ticks apart: the wave decides as one)
+                ok = 0;
+                break;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        if (threadIdx.x == 0) {
+            if (!ok) atomicOr(s.status, 1);
+            *verdict = ok;
         }
     }
-    if (!ok && threadIdx.x == 0) atomicOr(s.status, 1);
-    __threadfence();  // acquire: what the other workgroups stored before raising their flags is read from memory
-    return ok;
+    __syncthreads();
+    return *verdict != 0;
 }
 
 __device__ __forceinline__ f16x8 as_frag(const u32x4& v) { return __builtin_bit_cast(f16x8, v); }
@@ -86,13 +97,18 @@ struct LstmFwdArgs {
 };
 
 __global__ __launch_bounds__(RL_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1))) void lstm_layer_fwd_kernel(LstmFwdArgs a) {
-    __shared__ float red[4][32][65];  // per wave: partial gate sums [batch row][16 g + unit]
+    __shared__ float red[4][16][65];  // per wave: partial gate sums [batch row][16 g + unit]
+    __shared__ int   verdict;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 15, lq = lane >> 4;
     const int H = a.H, I = a.I, B = a.B, T = a.T;
-    const int j0  = blockIdx.x * RL_UNITS;
+    const int j0  = blockIdx.x * RL_UNITS;   // this workgroup's hidden units
+    const int b0  = blockIdx.y * RL_ROWS;    // ... and batch rows (the recurrence never mixes batch rows)
+    const int nb  = min(RL_ROWS, B - b0);
     const int Kw  = H >> 2;             // this wave's share of the contraction over h
     const int nks = Kw >> 5;            // matrix-core steps of 32
     const int k0  = wave * Kw + 8 * lq; // first k of this lane's 8 consecutive values, + 32 ks
+    RlSync    sync = a.sync;
+    sync.flags += blockIdx.y * RL_FLAG_WORDS;  // one barrier group per block of batch rows
 
     // W_h fragments, resident for the whole sequence: gate g, unit lr, 8 consecutive k
     u32x4 wf[4][8];
@@ -104,90 +120,66 @@ __global__ __launch_bounds__(RL_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1
             if (ks < nks) wf[g][ks] = *reinterpret_cast<const u32x4*>(a.w + (long long)(g * H + j0 + lr) * a.ldw + I + k0 + 32 * ks);
         }
 
-    // cell ownership: thread -> batch row cb, units cu, cu + 1
-    const int  cb = tid >> 3, cu = (tid & 7) * 2;
-    const bool cell = cb < B;
-    float      cst[2] = {0.f, 0.f}, bia[4][2];
+    // cell ownership: thread -> batch row b0 + cr, unit j0 + cu
+    const int  cr = tid >> 4, cu = tid & 15;
+    const bool cell = cr < nb;
+    float      cst = 0.f, bia[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        bia[g][0] = h2f(a.bias[g * H + j0 + cu]);
-        bia[g][1] = h2f(a.bias[g * H + j0 + cu + 1]);
-    }
-    if (cell) {
-        cst[0] = a.c[(long long)cb * H + j0 + cu];
-        cst[1] = a.c[(long long)cb * H + j0 + cu + 1];
-    }
+    for (int g = 0; g < 4; ++g) bia[g] = h2f(a.bias[g * H + j0 + cu]);
+    if (cell) cst = a.c[(long long)(b0 + cr) * H + j0 + cu];
 
     for (int t = 0; t < T; ++t) {
-        const long long row0 = (long long)t * B;
+        const long long row0 = (long long)t * B + b0;
         // the input half of this thread's gate sums does not depend on the recurrence: request it ahead of the wait
-        float gxv[4][2];
+        float gxv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (cell) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            gxv[g][0] = gxv[g][1] = 0.f;
-            if (cell) {
-                const float2 v = *reinterpret_cast<const float2*>(a.gx + (row0 + cb) * 4 * H + g * H + j0 + cu);
-                gxv[g][0] = v.x;
-                gxv[g][1] = v.y;
-            }
+            for (int g = 0; g < 4; ++g) gxv[g] = a.gx[(row0 + cr) * 4 * H + g * H + j0 + cu];
         }
-        if (t > 0 && !grid_wait(a.sync, t)) return;  // every workgroup's slice of h_{t-1} is in memory
+        if (t > 0 && !grid_wait(sync, t, &verdict)) return;  // every workgroup's slice of h_{t-1} (these rows) is in memory
         const uint16_t* hprev = a.xh + row0 * a.ldxh + I;
-        u32x4           af[2][8];
+        u32x4           af[8];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int ks = 0; ks < 8; ++ks) {
+            af[ks] = u32x4{0u, 0u, 0u, 0u};
+            if (ks < nks && lr < nb) af[ks] = *reinterpret_cast<const u32x4*>(hprev + (long long)lr * a.ldxh + k0 + 32 * ks);
+        }
+        f32x4 acc[4];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                af[mb][ks] = u32x4{0u, 0u, 0u, 0u};
-                if (ks < nks && 16 * mb + lr < B)
-                    af[mb][ks] = *reinterpret_cast<const u32x4*>(hprev + (long long)(16 * mb + lr) * a.ldxh + k0 + 32 * ks);
-            }
-        f32x4 acc[4][2];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) acc[g][0] = acc[g][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             if (ks < nks) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
-                        if (16 * mb < B)
-                            acc[g][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_frag(wf[g][ks]), as_frag(af[mb][ks]), acc[g][mb], 0, 0, 0);
+                    acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_frag(wf[g][ks]), as_frag(af[ks]), acc[g], 0, 0, 0);
             }
         }
-        // acc[g][mb][r] = partial sum of gate g, unit 4 lq + r, batch row 16 mb + lr
+        // acc[g][r] = partial sum of gate g, unit 4 lq + r, batch row lr
 #pragma unroll
         for (int g = 0; g < 4; ++g)
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) red[wave][16 * mb + lr][16 * g + 4 * lq + r] = acc[g][mb][r];
+            for (int r = 0; r < 4; ++r) red[wave][lr][16 * g + 4 * lq + r] = acc[g][r];
         __syncthreads();
         if (cell) {
-            uint16_t g16[4][2], h16[2];
+            uint16_t g16[4], h16;
+            float    gs[4];
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                float gs[4];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = 16 * g + cu + e;
-                    const float s = ((red[0][cb][n] + red[1][cb][n]) + red[2][cb][n]) + red[3][cb][n];
-                    g16[g][e]     = f2h((s + gxv[g][e]) + bia[g][e]);  // the gate sum's one rounding to storage
-                    gs[g]         = h2f(g16[g][e]);
-                }
-                cst[e] = lstm_cell_forward(gs[0], gs[1], gs[2], gs[3], cst[e], &h16[e]);
+            for (int g = 0; g < 4; ++g) {
+                const int   n = 16 * g + cu;
+                const float s = ((red[0][cr][n] + red[1][cr][n]) + red[2][cr][n]) + red[3][cr][n];
+                g16[g]        = f2h((s + gxv[g]) + bia[g]);  // the gate sum's one rounding to storage
+                gs[g]         = h2f(g16[g]);
             }
-            const long long row = row0 + cb;
+            cst = lstm_cell_forward(gs[0], gs[1], gs[2], gs[3], cst, &h16);
+            const long long row = row0 + cr;
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                *reinterpret_cast<unsigned*>(a.gates + row * 4 * H + g * H + j0 + cu) = (unsigned)g16[g][0] | ((unsigned)g16[g][1] << 16);
-            *reinterpret_cast<float2*>(a.c + (row + B) * H + j0 + cu) = make_float2(cst[0], cst[1]);
-            const unsigned hp = (unsigned)h16[0] | ((unsigned)h16[1] << 16);
-            if (t + 1 < T) *reinterpret_cast<unsigned*>(a.xh + (row + B) * a.ldxh + I + j0 + cu) = hp;
-            if (a.h_up != nullptr) *reinterpret_cast<unsigned*>(a.h_up + row * a.ld_up + j0 + cu) = hp;
+            for (int g = 0; g < 4; ++g) a.gates[row * 4 * H + g * H + j0 + cu] = g16[g];
+            a.c[(row + B) * H + j0 + cu] = cst;
+            if (t + 1 < T) a.xh[(row + B) * a.ldxh + I + j0 + cu] = h16;
+            if (a.h_up != nullptr) a.h_up[row * a.ld_up + j0 + cu] = h16;
         }
-        if (t + 1 < T) grid_arrive(a.sync, t + 1);  // (its workgroup barrier also keeps `red` of this step apart from the next)
+        if (t + 1 < T) grid_arrive(sync, t + 1);  // (its workgroup barrier also keeps `red` of this step apart from the next)
     }
 }
 
@@ -205,12 +197,17 @@ struct LstmBwdArgs {
 };
 
 __global__ __launch_bounds__(RL_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1))) void lstm_layer_bwd_kernel(LstmBwdArgs a) {
-    __shared__ float red[4][32][17];  // per wave: partial recurrent gradient [batch row][unit]
+    __shared__ float red[4][16][17];  // per wave: partial recurrent gradient [batch row][unit]
+    __shared__ int   verdict;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 15, lq = lane >> 4;
     const int H = a.H, I = a.I, B = a.B, T = a.T;
     const int j0  = blockIdx.x * RL_UNITS;
+    const int b0  = blockIdx.y * RL_ROWS;
+    const int nb  = min(RL_ROWS, B - b0);
     const int nks = H >> 5;                // this wave contracts over the H rows of gate block `wave`, 32 at a time
     const int n0  = wave * H + 8 * lq;     // first gate row of this lane's 8 consecutive values, + 32 ks
+    RlSync    sync = a.sync;
+    sync.flags += blockIdx.y * RL_FLAG_WORDS;
 
     // W_h^T fragments: unit lr, 8 consecutive gate rows n: W[n][I + j0 + lr] (a strided gather, once per launch)
     u32x4 wt[32];
@@ -227,73 +224,63 @@ __global__ __launch_bounds__(RL_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1
         }
     }
 
-    const int  cb = tid >> 3, cu = (tid & 7) * 2;
-    const bool cell = cb < B;
-    float      dc[2] = {0.f, 0.f}, dhrec[2] = {0.f, 0.f};
+    const int  cr = tid >> 4, cu = tid & 15;
+    const bool cell = cr < nb;
+    float      dc = 0.f, dhrec = 0.f;
+
+    // inputs of one cell-backward step for this thread's cell (they do not depend on the recurrence, so the next
+    // step's are requested while the workgroup waits at the step barrier)
+    struct CellIn {
+        uint16_t gp[4], da;
+        float    cp, cn;
+    };
+    auto load_cell = [&](int t) {
+        CellIn q{};
+        if (cell) {
+            const long long row = (long long)t * B + b0 + cr;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) q.gp[g] = a.gates[row * 4 * H + g * H + j0 + cu];
+            q.cp = a.c[row * H + j0 + cu];
+            q.cn = a.c[(row + B) * H + j0 + cu];
+            q.da = a.dh_above[row * a.ld_above + j0 + cu];
+        }
+        return q;
+    };
+    CellIn in = load_cell(T - 1);
 
     for (int t = T - 1; t >= 0; --t) {
-        const long long row = (long long)t * B + cb;
+        const long long row0 = (long long)t * B + b0;
         if (cell) {
-            unsigned gp[4], dp[4] = {0u, 0u, 0u, 0u};
+            uint16_t d4[4];
+            dc = lstm_cell_backward(h2f(in.gp[0]), h2f(in.gp[1]), h2f(in.gp[2]), h2f(in.gp[3]), in.cp, in.cn, h2f(in.da) + dhrec, dc, d4);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) gp[g] = *reinterpret_cast<const unsigned*>(a.gates + row * 4 * H + g * H + j0 + cu);
-            const float2   cp = *reinterpret_cast<const float2*>(a.c + row * H + j0 + cu);
-            const float2   cn = *reinterpret_cast<const float2*>(a.c + (row + B) * H + j0 + cu);
-            const unsigned da = *reinterpret_cast<const unsigned*>(a.dh_above + row * a.ld_above + j0 + cu);
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int sh = 16 * e;
-                const float dh = h2f((uint16_t)(da >> sh)) + dhrec[e];
-                uint16_t    d4[4];
-                dc[e] = lstm_cell_backward(h2f((uint16_t)(gp[0] >> sh)), h2f((uint16_t)(gp[1] >> sh)), h2f((uint16_t)(gp[2] >> sh)),
-                                           h2f((uint16_t)(gp[3] >> sh)), e ? cp.y : cp.x, e ? cn.y : cn.x, dh, dc[e], d4);
-#pragma unroll
-                for (int g = 0; g < 4; ++g) dp[g] |= (unsigned)d4[g] << sh;
-            }
-#pragma unroll
-            for (int g = 0; g < 4; ++g) *reinterpret_cast<unsigned*>(a.dgates + row * 4 * H + g * H + j0 + cu) = dp[g];
+            for (int g = 0; g < 4; ++g) a.dgates[(row0 + cr) * 4 * H + g * H + j0 + cu] = d4[g];
         }
         if (t == 0) break;
         const int step = T - t;                       // 1 .. T-1
-        grid_arrive(a.sync, step);
-        if (!grid_wait(a.sync, step)) return;         // the whole dgates_t is in memory
-        // recurrent gradient of this workgroup's units: dgates_t[B, 4H] W_h[:, j0 .. j0+16)
-        const uint16_t* dg = a.dgates + (long long)t * B * 4 * H;
-        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        grid_arrive(sync, step);
+        in = load_cell(t - 1);
+        if (!grid_wait(sync, step, &verdict)) return;           // these rows of dgates_t are complete in memory
+        // recurrent gradient of this workgroup's units: dgates_t[rows, 4H] W_h[:, j0 .. j0+16).  All of this lane's
+        // pieces of dgates_t are requested at once (one memory latency), then multiplied.
+        const uint16_t* dg = a.dgates + row0 * 4 * H;
+        u32x4           af[32];
 #pragma unroll
-        for (int ch = 0; ch < 4; ++ch) {              // chunks of 8 matrix-core steps: 16 loads in flight per lane
-            if (8 * ch < nks) {
-                u32x4 af[2][8];
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        af[mb][k] = u32x4{0u, 0u, 0u, 0u};
-                        if (8 * ch + k < nks && 16 * mb + lr < B)
-                            af[mb][k] = *reinterpret_cast<const u32x4*>(dg + (long long)(16 * mb + lr) * 4 * H + n0 + 32 * (8 * ch + k));
-                    }
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (8 * ch + k < nks) {
-#pragma unroll
-                        for (int mb = 0; mb < 2; ++mb)
-                            if (16 * mb < B)
-                                acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_frag(wt[8 * ch + k]), as_frag(af[mb][k]), acc[mb], 0, 0, 0);
-                    }
-            }
+        for (int ks = 0; ks < 32; ++ks) {
+            af[ks] = u32x4{0u, 0u, 0u, 0u};
+            if (ks < nks && lr < nb) af[ks] = *reinterpret_cast<const u32x4*>(dg + (long long)lr * 4 * H + n0 + 32 * ks);
         }
-        // acc[mb][r] = partial sum for unit 4 lq + r, batch row 16 mb + lr
+        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};  // two chains: even and odd steps
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int ks = 0; ks < 32; ++ks)
+            if (ks < nks) acc[ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_frag(wt[ks]), as_frag(af[ks]), acc[ks & 1], 0, 0, 0);
+        // acc[.][r] = partial sum for unit 4 lq + r, batch row lr
 #pragma unroll
-            for (int r = 0; r < 4; ++r) red[wave][16 * mb + lr][4 * lq + r] = acc[mb][r];
+        for (int r = 0; r < 4; ++r) red[wave][lr][4 * lq + r] = acc[0][r] + acc[1][r];
         __syncthreads();
         if (cell) {
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const float s = ((red[0][cb][cu + e] + red[1][cb][cu + e]) + red[2][cb][cu + e]) + red[3][cb][cu + e];
-                dhrec[e]      = round16(s);          // the recurrent gradient is a stored (fp16) tensor
-            }
+            const float s = ((red[0][cr][cu] + red[1][cr][cu]) + red[2][cr][cu]) + red[3][cr][cu];
+            dhrec         = round16(s);              // the recurrent gradient is a stored (fp16) tensor
         }
         // (`red` is next written behind the next step's barrier)
     }
@@ -320,14 +307,16 @@ static int rl_check(const mp_lstm_layer_desc* d, const char* who, int* nwg) {
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return hip_fail(e, who);
     *nwg = d->H / RL_UNITS;
-    if (*nwg > cus) {  // every workgroup must be resident at once, or the step barrier cannot complete
-        set_error("%s: %d workgroups needed, the device has %d compute units", who, *nwg, cus);
+    const int groups = (d->B + RL_ROWS - 1) / RL_ROWS;
+    if (*nwg * groups > cus) {  // every workgroup must be resident at once, or the step barrier cannot complete
+        set_error("%s: %d workgroups needed, the device has %d compute units", who, *nwg * groups, cus);
         return MP_E_UNSUPPORTED;
     }
     return MP_OK;
 }
 
-extern "C" size_t mp_lstm_layer_workspace_bytes(void) { return 1024; }  // step flags: up to 64 workgroups + 64 debug words
+// step flags: two barrier groups (B <= 32 rows in blocks of 16) of up to 64 workgroups + 64 debug words each
+extern "C" size_t mp_lstm_layer_workspace_bytes(void) { return 2 * RL_FLAG_WORDS * sizeof(int); }
 
 static int rl_sync(const mp_lstm_layer_desc* d, int nwg, int32_t* status, void* ws, size_t ws_bytes, mp_stream stream,
                    const char* who, RlSync* out) {
@@ -361,7 +350,7 @@ extern "C" int mp_lstm_layer_fwd(const mp_lstm_layer_desc* d, const float* gx, c
     a.T = d->T; a.B = d->B; a.I = d->I; a.H = d->H;
     a.gx = gx; a.w = w; a.ldw = d->ldw; a.bias = bias; a.gates = gates; a.c = c; a.xh = xh; a.ldxh = d->ldxh;
     a.h_up = h_up; a.ld_up = d->ld_up;
-    hipLaunchKernelGGL(lstm_layer_fwd_kernel, dim3(nwg), dim3(RL_THREADS), 0, as_stream(stream), a);
+    hipLaunchKernelGGL(lstm_layer_fwd_kernel, dim3(nwg, (d->B + RL_ROWS - 1) / RL_ROWS), dim3(RL_THREADS), 0, as_stream(stream), a);
     MP_LAUNCH_CHECK("mp_lstm_layer_fwd");
     return MP_OK;
 }
@@ -381,7 +370,7 @@ extern "C" int mp_lstm_layer_bwd(const mp_lstm_layer_desc* d, const mp_half* w, 
     if (rc) return rc;
     a.T = d->T; a.B = d->B; a.I = d->I; a.H = d->H;
     a.w = w; a.ldw = d->ldw; a.gates = gates; a.c = c; a.dh_above = dh_above; a.ld_above = d->ld_up; a.dgates = dgates;
-    hipLaunchKernelGGL(lstm_layer_bwd_kernel, dim3(nwg), dim3(RL_THREADS), 0, as_stream(stream), a);
+    hipLaunchKernelGGL(lstm_layer_bwd_kernel, dim3(nwg, (d->B + RL_ROWS - 1) / RL_ROWS), dim3(RL_THREADS), 0, as_stream(stream), a);
     MP_LAUNCH_CHECK("mp_lstm_layer_bwd");
     return MP_OK;
 }
