@@ -35,8 +35,9 @@
  *     (split contractions, column sums, the update over many tensors) may leave the
  *     earlier launches enqueued: treat the outputs as undefined.
  *   - The library keeps no state between calls, with two documented exceptions that are
- *     measurement aids and not part of a training step: mp_gemm_tuning_override (a
- *     process-wide, not thread-safe tile choice for sweeps) and mp_mfma_sustained_rate
+ *     measurement aids and not part of a training step: mp_gemm_tuning_override /
+ *     mp_gemm_tuning_dtl (process-wide, not thread-safe kernel choices for sweeps and
+ *     tests) and mp_mfma_sustained_rate
  *     (the ONE call that blocks: it times its own launch with events).
  *   - Scratch ("workspace") is caller-provided device memory; each call that needs it
  *     has a *_workspace_bytes query.  Contents need not be initialised and are
@@ -209,6 +210,12 @@ int mp_gemm_bwd_dw_grouped(const mp_gemm_group_item* items, int count, mp_scale_
  * summation order.
  * Note that mp_gemm_bwd_dw_workspace_bytes answers for the choice in force when it is called. */
 int mp_gemm_tuning_override(int tile, int splits);
+
+/* Tuning aid of the same kind (process-wide, not thread-safe, never called by a training step): which interior,
+ * unbatched, unsplit products run on the kernels whose operand tiles go from global memory straight into LDS.
+ * 0 = none, 1 = weight-gradient products only (the built-in choice), 2 = every product they are built for (all three
+ * operand layouts).  Same results contract either way (fp32 summation order may differ).  Other values: MP_E_INVAL. */
+int mp_gemm_tuning_dtl(int mode);
 
 /* db[cols] = RNE16( column sums (fp32) of dY[rows, cols] ); optional overflow flag as above.
  * Workspace: mp_colsum_workspace_bytes(rows, cols). */

@@ -69,6 +69,7 @@ SIGNATURES = {
     "mp_gemm_bwd_dx_ws": (_I, [C.POINTER(GemmDesc), _P, _P, _P, _P, C.c_int32, _P, _P, _SZ, _P]),
     "mp_gemm_bwd_dw_grouped": (_I, [C.POINTER(GemmGroupItem), _I, _P, _P]),
     "mp_gemm_tuning_override": (_I, [_I, _I]),
+    "mp_gemm_tuning_dtl": (_I, [_I]),
     "mp_colsum_workspace_bytes": (_SZ, [_I, _I]),
     "mp_colsum": (_I, [_I, _I, _P, _I, _P, _P, _P, _SZ, _P]),
     "mp_colsum_static_max_bytes": (_SZ, []),

@@ -126,6 +126,10 @@ def mp_gemm_tuning_override(tile: int, splits: int = 1):
     _check(L.load().mp_gemm_tuning_override(tile, splits))
 
 
+def mp_gemm_tuning_dtl(mode: int):
+    _check(L.load().mp_gemm_tuning_dtl(mode))
+
+
 def mp_colsum_workspace_bytes(rows: int, cols: int) -> int:
     return L.load().mp_colsum_workspace_bytes(rows, cols)
 

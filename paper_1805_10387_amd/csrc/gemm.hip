@@ -1,6 +1,6 @@
 // Contractions: planner, split-K finish, generic fallback and the C entry points.  The matrix-core kernel templates are
 // in gemm_kernels.hpp and are instantiated in gemm_kk.hip / gemm_ko.hip / gemm_oo.hip.
-#include "gemm_kernels.hpp"
+#include "gemm_dtl.hpp"
 
 #include <cstdlib>
 #include <cstring>
@@ -10,8 +10,13 @@ namespace mp {
 extern template int launch_tile<true, true>(int, const GemmArgs&, dim3, hipStream_t);
 extern template int launch_tile<true, false>(int, const GemmArgs&, dim3, hipStream_t);
 extern template int launch_tile<false, false>(int, const GemmArgs&, dim3, hipStream_t);
+extern template int launch_dtl_tile<true, true>(int, const GemmArgs&, int, hipStream_t);
+extern template int launch_dtl_tile<true, false>(int, const GemmArgs&, int, hipStream_t);
+extern template int launch_dtl_tile<false, false>(int, const GemmArgs&, int, hipStream_t);
 extern template int launch_grouped<256, 256>(const GroupArgs&, int, hipStream_t);
 extern template int launch_grouped<128, 128>(const GroupArgs&, int, hipStream_t);
+extern template int launch_dtl_grouped<256, 256>(const GroupArgs&, int, hipStream_t);
+extern template int launch_dtl_grouped<128, 128>(const GroupArgs&, int, hipStream_t);
 
 // Sum split-K partials in split order, scale, round once, optional non-finite flag.
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ part, int splits, long long mn,
@@ -98,6 +103,11 @@ struct Plan {
 };
 static int g_force_tile = -1, g_force_splits = 1;
 
+// Which products take the direct-to-LDS kernels (mp_gemm_tuning_dtl): 0 = none, 1 (default) = weight-gradient products
+// (both operands output-contiguous), 2 = every product they are built for.
+static int g_dtl_mode = 1;
+static int dtl_mode() { return g_dtl_mode; }
+
 // Pick the tile shape (and split count when allowed) that minimises an estimate of run time:
 // rounds of 256 workgroups x work per workgroup / shape efficiency.
 static Plan make_plan(int M, int N, int K, long long batches, bool allow_split, bool kc_kc = false) {
@@ -181,6 +191,18 @@ static int run_gemm(GemmArgs g, bool a_kc, bool b_kc, long long batches, bool al
     const int  gx = (others == 1 && ntiles > resident) ? resident : ntiles;
     const dim3 grid((unsigned)gx, (unsigned)batches, (unsigned)p.splits);
 
+    // interior, unbatched, unsplit problems on the large tiles: operands go straight from global memory into LDS
+    // (built for all three operand layouts, used where it is the faster one: both operands output-contiguous, i.e. the
+    // weight gradients.  A contraction-contiguous operand arrives there in 64-byte row pieces, which costs what the
+    // saved LDS stores gain, so forward and input-gradient products stay on the register-staged kernel)
+    const int bm = kTiles[p.tile].bm, bn = kTiles[p.tile].bn;
+    if (dtl_mode() != 0 && others == 1 && bm >= 128 && bn >= 128 && g.M % bm == 0 && g.N % bn == 0 && g.K % DK == 0 && g.K >= DK &&
+        (a_kc || !b_kc) && (dtl_mode() == 2 || (!a_kc && !b_kc))) {
+        const int gxd = ntiles > kCUs ? kCUs : ntiles;   // one workgroup per compute unit (its ring of stages fills the LDS)
+        if (a_kc && b_kc) return launch_dtl_tile<true, true>(p.tile, g, gxd, hs);
+        if (a_kc && !b_kc) return launch_dtl_tile<true, false>(p.tile, g, gxd, hs);
+        return launch_dtl_tile<false, false>(p.tile, g, gxd, hs);
+    }
     GemmArgs k = g;
     if (p.splits > 1) {  // partials to workspace, epilogue (scale, bias, rounding, flag) in the finish kernel
         k.C32       = ws;
@@ -246,6 +268,12 @@ extern "C" int mp_gemm_tuning_override(int tile, int splits) {
     MP_REQUIRE(tile < 0 || (splits >= 0 && splits <= 16), "mp_gemm_tuning_override: splits %d outside 0..16", splits);
     g_force_tile   = tile;
     g_force_splits = splits > 0 ? splits : 1;
+    return MP_OK;
+}
+
+extern "C" int mp_gemm_tuning_dtl(int mode) {
+    MP_REQUIRE(mode >= 0 && mode <= 2, "mp_gemm_tuning_dtl: mode %d outside 0..2", mode);
+    g_dtl_mode = mode;
     return MP_OK;
 }
 
@@ -416,5 +444,9 @@ extern "C" int mp_gemm_bwd_dw_grouped(const mp_gemm_group_item* items, int count
     }
     MP_REQUIRE(total < (1 << 24), "mp_gemm_bwd_dw_grouped: too many tiles");
     for (int i = count; i <= GROUP_MAX; ++i) ga.tile_start[i] = (int)total;
+    bool k32 = true;
+    for (int i = 0; i < count; ++i) k32 = k32 && ga.p[i].K % DK == 0;
+    if (dtl_mode() != 0 && k32)
+        return all256 ? launch_dtl_grouped<256, 256>(ga, kCUs, as_stream(stream)) : launch_dtl_grouped<128, 128>(ga, kCUs, as_stream(stream));
     return all256 ? launch_grouped<256, 256>(ga, kCUs, as_stream(stream)) : launch_grouped<128, 128>(ga, 2 * kCUs, as_stream(stream));
 }

@@ -225,6 +225,142 @@ struct OperandStream {
     }
 };
 
+// ---- epilogue of one wave tile (TM x TN matrix-core tiles of 32 x 32), in the layout the matrix cores leave the result
+// in.  mrow = first output row of this lane (row of the wave tile + lane % 32), ncol = first column of the wave tile.
+template <int TM, int TN, bool EDGE>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16 (&acc)[TM][TN], const int mrow, const int ncol,
+                                              const int bo, const int bi, const int bz, const bool split,
+                                              const bool fold_bias, bool& bad) {
+    const int eh = (threadIdx.x & 63) >> 5;
+    // ---- epilogue, in the layout the matrix cores leave the result in.  Of the 32x32 tile (i, j) lane
+    // (er = lane % 32, eh = lane / 32) holds row er and, for q = 0..3, the 4 consecutive columns 8 q + 4 eh ...
+    // (acc[i][j][4 q + c]).  fp32 outputs are stored from there, 16 bytes per lane.  fp16 outputs are converted
+    // and packed in pairs, then lanes er and er + 32 trade halves (one cross-half register swap per packed pair)
+    // so that each lane ends up with 8 consecutive columns: 16-byte stores, and 16-byte loads of the residual /
+    // ReLU-source operand, without a trip through LDS.
+    asm volatile("s_nop 15\n\ts_nop 15");  // the last matrix-core results have landed before the explicit accumulator reads
+    uint16_t*       C   = g.C ? g.C + bo * g.sc_o + bi * g.sc_i : nullptr;
+    const uint16_t* aux = g.relu_src ? g.relu_src : g.add;
+    if (aux) aux += bo * g.sc_o + bi * g.sc_i;
+    float*     C32   = g.C32 ? g.C32 + (long long)bz * g.M * g.N : nullptr;
+
+    // (N is a multiple of 8 on this path, so a 16-byte piece of a row is either fully inside or fully outside)
+    if (C32) {  // raw accumulator out: split-K partial, or fp32 result with alpha and addend
+        static_for<TM * TN * 4>([&](auto tc) {
+            constexpr int t = decltype(tc)::value, i = t / (TN * 4), j = (t / 4) % TN, q = t % 4;
+            const int m = mrow + 32 * i, n = ncol + 32 * j + 8 * q + 4 * eh;
+            if (EDGE && (m >= g.M || n >= g.N)) return;
+            f32x4 v = {acc_get(acc[i][j][4 * q]), acc_get(acc[i][j][4 * q + 1]), acc_get(acc[i][j][4 * q + 2]), acc_get(acc[i][j][4 * q + 3])};
+            const long long mn = (long long)m * g.N + n;
+            if (!split) {
+                v *= g.alpha;
+                if (g.acc_in) v += *reinterpret_cast<const f32x4*>(g.acc_in + mn);
+            }
+            *reinterpret_cast<f32x4*>(C32 + mn) = v;
+        });
+    } else {
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        typedef float    f32x2 __attribute__((ext_vector_type(2)));
+        typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+        // the uncommon terms first, in fp32: scale factor, fp32 addend, a bias that could not start the accumulators
+        if (g.alpha != 1.f || g.acc_in || (g.bias && !fold_bias)) {
+            static_for<TM * TN * 4>([&](auto tc) {
+                constexpr int t = decltype(tc)::value, i = t / (TN * 4), j = (t / 4) % TN, q = t % 4;
+                const int m = mrow + 32 * i, n = ncol + 32 * j + 8 * q + 4 * eh;
+                const bool in = !EDGE || (m < g.M && n < g.N);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float x = acc_get(acc[i][j][4 * q + e]) * g.alpha;
+                    if (g.acc_in && in) x += g.acc_in[(long long)m * g.N + n + e];
+                    if (g.bias && !fold_bias && in) x += h2f(g.bias[n + e]);
+                    acc[i][j][4 * q + e] = acc_put(x);
+                }
+            });
+        }
+        constexpr int NCH = TN * 2;  // 16-byte pieces per lane and 32-row block: tile j, piece c -> columns 32 j + 16 c + 8 eh ...
+        u16x2         mag = {0, 0};  // running maximum of the magnitude bits of everything stored (non-finite: >= 0x7C00)
+        // residual / ReLU-source pieces of block i; those of block i + 1 are requested before block i is worked on
+        u32x4 av[2][NCH];
+        auto  aux_load = [&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            static_for<NCH>([&](auto cc) {
+                constexpr int ch = decltype(cc)::value;
+                const int     m = mrow + 32 * i, n = ncol + 16 * ch + 8 * eh;
+                av[i & 1][ch]   = u32x4{0u, 0u, 0u, 0u};
+                if (!EDGE || (m < g.M && n < g.N)) av[i & 1][ch] = *reinterpret_cast<const u32x4*>(aux + (long long)m * g.ld_aux + n);
+            });
+        };
+        if (aux) aux_load(std::integral_constant<int, 0>{});
+        static_for<TM>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            if constexpr (i + 1 < TM) {
+                if (aux) aux_load(std::integral_constant<int, i + 1>{});
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int m = mrow + 32 * i;
+            static_for<TN>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                float         v[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) v[e] = acc_get(acc[i][j][e]);
+                if (g.relu) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) v[e] = (v[e] < 0.f) ? 0.f : v[e];  // max(v, 0) that keeps a NaN (the comparison is false for it)
+                }
+                // one rounding to fp16, packed in pairs: d[2 q], d[2 q + 1] = columns 8 q + 4 eh + {0, 1}, {2, 3}
+                unsigned d[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const f16x2 hpair = __builtin_convertvector(f32x2{v[2 * e], v[2 * e + 1]}, f16x2);
+                    d[e]              = __builtin_bit_cast(unsigned, hpair);
+                }
+                // lanes er (eh = 0) and er + 32 (eh = 1) trade: afterwards d[4 c .. 4 c + 3] hold, in order, the 8
+                // consecutive columns 16 c + 8 eh ... of row er
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int w = 0; w < 2; ++w) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(d[4 * c + w], d[4 * c + 2 + w], false, false);
+                        d[4 * c + w]     = sw[0];
+                        d[4 * c + 2 + w] = sw[1];
+                    }
+                static_for<2>([&](auto cc) {
+                    constexpr int c = decltype(cc)::value;
+                    const int     n = ncol + 32 * j + 16 * c + 8 * eh;
+                    if (EDGE && (m >= g.M || n >= g.N)) return;
+                    u32x4 out = {d[4 * c], d[4 * c + 1], d[4 * c + 2], d[4 * c + 3]};
+                    if (aux) {
+                        const u32x4 a = av[i & 1][2 * j + c];
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            const unsigned ow = out[w], aw = a[w];  // (bit_cast wants whole objects, not vector elements)
+                            const f16x2    hv = __builtin_bit_cast(f16x2, ow), tv = __builtin_bit_cast(f16x2, aw);
+                            f16x2       rv;
+                            if (g.relu_src) {
+                                rv[0] = (tv[0] > (_Float16)0) ? hv[0] : (_Float16)0;
+                                rv[1] = (tv[1] > (_Float16)0) ? hv[1] : (_Float16)0;
+                            } else {
+                                rv = __builtin_convertvector(__builtin_convertvector(hv, f32x2) + __builtin_convertvector(tv, f32x2), f16x2);
+                            }
+                            out[w] = __builtin_bit_cast(unsigned, rv);
+                        }
+                    }
+                    if (g.found_inf) {
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            const unsigned mw = out[w] & 0x7FFF7FFFu;
+                            mag               = __builtin_elementwise_max(mag, __builtin_bit_cast(u16x2, mw));
+                        }
+                    }
+                    *reinterpret_cast<u32x4*>(C + (long long)m * g.ldc + n) = out;
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        bad |= mag[0] >= 0x7C00 || mag[1] >= 0x7C00;
+    }
+}
+
 // One output tile: tile number `pid` of problem g (tiles are numbered in bands of GROUP tile-rows), batch `by`, k-split
 // `bz` of `nz`; `pid_next` is the tile this workgroup takes afterwards (same problem, batch and split), or -1.
 // EDGE = false: every tile lies fully inside the matrices and K is a multiple of BK, so neither the
@@ -440,135 +576,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int pid, cons
     S.primed = chain;
     if (chain && fold_bias) load_bias(ncol1);
 
-    // ---- epilogue, in the layout the matrix cores leave the result in.  Of the 32x32 tile (i, j) lane
-    // (er = lane % 32, eh = lane / 32) holds row er and, for q = 0..3, the 4 consecutive columns 8 q + 4 eh ...
-    // (acc[i][j][4 q + c]).  fp32 outputs are stored from there, 16 bytes per lane.  fp16 outputs are converted
-    // and packed in pairs, then lanes er and er + 32 trade halves (one cross-half register swap per packed pair)
-    // so that each lane ends up with 8 consecutive columns: 16-byte stores, and 16-byte loads of the residual /
-    // ReLU-source operand, without a trip through LDS.
-    asm volatile("s_nop 15\n\ts_nop 15");  // the last matrix-core results have landed before the explicit accumulator reads
-    uint16_t*       C   = g.C ? g.C + bo * g.sc_o + bi * g.sc_i : nullptr;
-    const uint16_t* aux = g.relu_src ? g.relu_src : g.add;
-    if (aux) aux += bo * g.sc_o + bi * g.sc_i;
-    float*     C32   = g.C32 ? g.C32 + (long long)bz * g.M * g.N : nullptr;
-    const bool split = nz > 1;
-    const int  mrow = m0 + wm * WM + er;  // + 32 i
-
-    // (N is a multiple of 8 on this path, so a 16-byte piece of a row is either fully inside or fully outside)
-    if (C32) {  // raw accumulator out: split-K partial, or fp32 result with alpha and addend
-        static_for<TM * TN * 4>([&](auto tc) {
-            constexpr int t = decltype(tc)::value, i = t / (TN * 4), j = (t / 4) % TN, q = t % 4;
-            const int m = mrow + 32 * i, n = ncol + 32 * j + 8 * q + 4 * eh;
-            if (EDGE && (m >= g.M || n >= g.N)) return;
-            f32x4 v = {acc_get(acc[i][j][4 * q]), acc_get(acc[i][j][4 * q + 1]), acc_get(acc[i][j][4 * q + 2]), acc_get(acc[i][j][4 * q + 3])};
-            const long long mn = (long long)m * g.N + n;
-            if (!split) {
-                v *= g.alpha;
-                if (g.acc_in) v += *reinterpret_cast<const f32x4*>(g.acc_in + mn);
-            }
-            *reinterpret_cast<f32x4*>(C32 + mn) = v;
-        });
-    } else {
-        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-        typedef float    f32x2 __attribute__((ext_vector_type(2)));
-        typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
-        // the uncommon terms first, in fp32: scale factor, fp32 addend, a bias that could not start the accumulators
-        if (g.alpha != 1.f || g.acc_in || (g.bias && !fold_bias)) {
-            static_for<TM * TN * 4>([&](auto tc) {
-                constexpr int t = decltype(tc)::value, i = t / (TN * 4), j = (t / 4) % TN, q = t % 4;
-                const int m = mrow + 32 * i, n = ncol + 32 * j + 8 * q + 4 * eh;
-                const bool in = !EDGE || (m < g.M && n < g.N);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float x = acc_get(acc[i][j][4 * q + e]) * g.alpha;
-                    if (g.acc_in && in) x += g.acc_in[(long long)m * g.N + n + e];
-                    if (g.bias && !fold_bias && in) x += h2f(g.bias[n + e]);
-                    acc[i][j][4 * q + e] = acc_put(x);
-                }
-            });
-        }
-        constexpr int NCH = TN * 2;  // 16-byte pieces per lane and 32-row block: tile j, piece c -> columns 32 j + 16 c + 8 eh ...
-        u16x2         mag = {0, 0};  // running maximum of the magnitude bits of everything stored (non-finite: >= 0x7C00)
-        // residual / ReLU-source pieces of block i; those of block i + 1 are requested before block i is worked on
-        u32x4 av[2][NCH];
-        auto  aux_load = [&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            static_for<NCH>([&](auto cc) {
-                constexpr int ch = decltype(cc)::value;
-                const int     m = mrow + 32 * i, n = ncol + 16 * ch + 8 * eh;
-                av[i & 1][ch]   = u32x4{0u, 0u, 0u, 0u};
-                if (!EDGE || (m < g.M && n < g.N)) av[i & 1][ch] = *reinterpret_cast<const u32x4*>(aux + (long long)m * g.ld_aux + n);
-            });
-        };
-        if (aux) aux_load(std::integral_constant<int, 0>{});
-        static_for<TM>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            if constexpr (i + 1 < TM) {
-                if (aux) aux_load(std::integral_constant<int, i + 1>{});
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            const int m = mrow + 32 * i;
-            static_for<TN>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                float         v[16];
-#pragma unroll
-                for (int e = 0; e < 16; ++e) v[e] = acc_get(acc[i][j][e]);
-                if (g.relu) {
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) v[e] = (v[e] < 0.f) ? 0.f : v[e];  // max(v, 0) that keeps a NaN (the comparison is false for it)
-                }
-                // one rounding to fp16, packed in pairs: d[2 q], d[2 q + 1] = columns 8 q + 4 eh + {0, 1}, {2, 3}
-                unsigned d[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const f16x2 hpair = __builtin_convertvector(f32x2{v[2 * e], v[2 * e + 1]}, f16x2);
-                    d[e]              = __builtin_bit_cast(unsigned, hpair);
-                }
-                // lanes er (eh = 0) and er + 32 (eh = 1) trade: afterwards d[4 c .. 4 c + 3] hold, in order, the 8
-                // consecutive columns 16 c + 8 eh ... of row er
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-#pragma unroll
-                    for (int w = 0; w < 2; ++w) {
-                        const auto sw = __builtin_amdgcn_permlane32_swap(d[4 * c + w], d[4 * c + 2 + w], false, false);
-                        d[4 * c + w]     = sw[0];
-                        d[4 * c + 2 + w] = sw[1];
-                    }
-                static_for<2>([&](auto cc) {
-                    constexpr int c = decltype(cc)::value;
-                    const int     n = ncol + 32 * j + 16 * c + 8 * eh;
-                    if (EDGE && (m >= g.M || n >= g.N)) return;
-                    u32x4 out = {d[4 * c], d[4 * c + 1], d[4 * c + 2], d[4 * c + 3]};
-                    if (aux) {
-                        const u32x4 a = av[i & 1][2 * j + c];
-#pragma unroll
-                        for (int w = 0; w < 4; ++w) {
-                            const unsigned ow = out[w], aw = a[w];  // (bit_cast wants whole objects, not vector elements)
-                            const f16x2    hv = __builtin_bit_cast(f16x2, ow), tv = __builtin_bit_cast(f16x2, aw);
-                            f16x2       rv;
-                            if (g.relu_src) {
-                                rv[0] = (tv[0] > (_Float16)0) ? hv[0] : (_Float16)0;
-                                rv[1] = (tv[1] > (_Float16)0) ? hv[1] : (_Float16)0;
-                            } else {
-                                rv = __builtin_convertvector(__builtin_convertvector(hv, f32x2) + __builtin_convertvector(tv, f32x2), f16x2);
-                            }
-                            out[w] = __builtin_bit_cast(unsigned, rv);
-                        }
-                    }
-                    if (g.found_inf) {
-#pragma unroll
-                        for (int w = 0; w < 4; ++w) {
-                            const unsigned mw = out[w] & 0x7FFF7FFFu;
-                            mag               = __builtin_elementwise_max(mag, __builtin_bit_cast(u16x2, mw));
-                        }
-                    }
-                    *reinterpret_cast<u32x4*>(C + (long long)m * g.ldc + n) = out;
-                });
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        });
-        bad |= mag[0] >= 0x7C00 || mag[1] >= 0x7C00;
-    }
+    gemm_epilogue<TM, TN, EDGE>(g, acc, m0 + wm * WM + er, ncol, bo, bi, bz, nz > 1, fold_bias, bad);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, bool EDGE>

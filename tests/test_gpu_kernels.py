@@ -86,6 +86,51 @@ def test_gemm_workgroups_that_take_several_tiles(tile, M, N, K):
     assert mp.scale_state_read(st).found_inf == 0
 
 
+@pytest.mark.parametrize("tile,M,N,K", [(0, 4352, 4096, 256), (0, 512, 512, 32), (0, 256, 768, 1056), (1, 2304, 1152, 96),
+                                        (2, 1152, 2304, 160), (3, 2560, 3456, 512), (3, 128, 128, 32), (8, 512, 384, 224)])
+def test_gemm_direct_to_lds_kernels_all_layouts(tile, M, N, K):
+    """The kernels whose operand tiles go from global memory straight into LDS (ring of 32-deep k-tiles; transposing LDS
+    reads for output-contiguous operands), forced for every product they are built for: forward (both operands
+    contraction-contiguous), dX (second operand output-contiguous) and dW (both output-contiguous), every tile shape,
+    one and several tiles per workgroup (the ring then runs on from tile to tile), k-tile counts below, at and above the
+    ring depth, with the epilogues that read a second operand and the overflow flag."""
+    r = RNG(M + N + K + tile + 3)
+    x, w, b = S16(r.standard_normal((M, K))), S16(r.standard_normal((N, K)) * 0.1), S16(r.standard_normal(N))
+    dy, src, other = S16(r.standard_normal((M, N))), S16(np.maximum(r.standard_normal((M, K)), 0)), S16(r.standard_normal((M, K)))
+    d = mp.gemm_desc(M, N, K, epilogue=2)
+    y, dx, dx2, dw = empty16(M, N), empty16(M, K), empty16(M, K), empty16(N, K)
+    st = make_state()
+    ws = ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, False))
+    mp.mp_gemm_tuning_override(tile, 1)
+    mp.mp_gemm_tuning_dtl(2)
+    try:
+        mp.mp_gemm_fwd(d, h16(x), h16(w), h16(b), None, y)
+        mp.mp_gemm_bwd_dx(mp.gemm_desc(M, N, K), h16(dy), h16(w), dx, relu_src=h16(src), ld_aux=K)
+        mp.mp_gemm_bwd_dx(mp.gemm_desc(M, N, K), h16(dy), h16(w), dx2, add=h16(other), ld_aux=K)
+        mp.mp_gemm_bwd_dw(mp.gemm_desc(M, N, K), h16(dy), h16(x), dw, None, st, ws)
+    finally:
+        mp.mp_gemm_tuning_override(-1, 0)
+        mp.mp_gemm_tuning_dtl(1)
+    assert_close16(y, L.linear_fwd(MIXED, x, w, b, relu=True), 1e-3, max_ulp=1, what="fwd")
+    base = MIXED.store(dy @ w)
+    assert_close16(dx, L.relu_mask(MIXED, base, src), 1e-3, max_ulp=1, what="dx relu")
+    assert_close16(dx2, L.add_store(MIXED, base, other), 1e-3, what="dx add")
+    assert_close16(dw, MIXED.store(dy.T @ x), 1e-3, max_ulp=1, what="dw")
+    assert mp.scale_state_read(st).found_inf == 0
+    # the same weight gradient with the kernels switched off: the register-staged path stays covered
+    dw0 = empty16(N, K)
+    mp.mp_gemm_tuning_override(tile if tile != 8 else 0, 1)
+    mp.mp_gemm_tuning_dtl(0)
+    try:
+        mp.mp_gemm_bwd_dw(mp.gemm_desc(M, N, K), h16(dy), h16(x), dw0, None, st, ws)
+    finally:
+        mp.mp_gemm_tuning_override(-1, 0)
+        mp.mp_gemm_tuning_dtl(1)
+    assert_close16(dw0, MIXED.store(dy.T @ x), 1e-3, max_ulp=1, what="dw, register-staged")
+    with pytest.raises(mp.MPError):
+        mp.mp_gemm_tuning_dtl(3)
+
+
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
 def test_gemm_bwd_dx_and_dw(M, N, K):
     r = RNG(M * 3 + N + K)
@@ -302,10 +347,17 @@ def test_gemm_grouped_weight_gradients(shapes):
         mp.mp_gemm_bwd_dw(d, items[-1][1], items[-1][2], dw1, None, None, ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, False)))
         mp.mp_gemm_tuning_override(-1, 0)
         singles.append(dw1)
-    mp.mp_gemm_bwd_dw_grouped(mp.gemm_group(items), st)
-    for k, (it, ref, one) in enumerate(zip(items, refs, singles)):
-        assert_close16(it[3], ref, 1e-3, max_ulp=1, what=f"grouped dw {k}")
-        assert torch.equal(it[3], one), f"grouped dw {k} differs from the single-problem result"
+    for mode in (1, 0):                                           # direct-to-LDS kernels (built-in choice), register-staged kernels
+        mp.mp_gemm_tuning_dtl(mode)
+        try:
+            for it in items:
+                it[3].zero_()
+            mp.mp_gemm_bwd_dw_grouped(mp.gemm_group(items), st)
+        finally:
+            mp.mp_gemm_tuning_dtl(1)
+        for k, (it, ref, one) in enumerate(zip(items, refs, singles)):
+            assert_close16(it[3], ref, 1e-3, max_ulp=1, what=f"grouped dw {k} (mode {mode})")
+            assert torch.equal(it[3], one), f"grouped dw {k} differs from the single-problem result (mode {mode})"
     assert mp.scale_state_read(st).found_inf == 0
 
 
