@@ -223,19 +223,76 @@ __global__ __launch_bounds__(AT_THREADS, 4) void attention_fwd_kernel(int n_head
 }
 
 // ------------------------------------------------------------------------------------ backward
-// LDS: Pt, dSt [128][128] (T[n][m]) plus one [64][128] buffer X that holds Kt for dQ, then dOt for dV, then Qt
-// for dK: 80 KiB, so two workgroups share a CU.
-constexpr int AT_BWD_LDS = 2 * 128 * 256 + 64 * 256;
+// Every matrix sits in LDS the way it sits in memory (row-major, staged with coalesced 16-byte accesses); whatever a
+// product needs transposed comes out of the transposing LDS read (`ds_read_b64_tr_b16`: within 16 lanes, the four
+// lanes 4 j .. 4 j + 3 address 8-byte chunks of matrix row k0 + j covering 16 consecutive columns, and lane i gets
+// column i of rows k0 .. k0 + 3), two reads per 8-deep matrix-core fragment.  No 2-byte LDS scatters, no transposing
+// stagings.
+// LDS: one [128][128] query-major buffer (32 KB) that holds P for the dV product and then dS for the dK product, plus one
+// [128][64] buffer X (16 KB) that holds the rows of V (dP), dO (dV), K (dQ) and Q (dK) in turn: 48 KiB; the matrix that
+// X takes next is always already on its way from memory in registers.  Two workgroups share a CU: the registers, not
+// the LDS, set that (a third workgroup per CU would leave 168 registers per lane, and the spills that costs took the
+// kernel from 36 to 65 us per layer).
+constexpr int AT_BWD_LDS = 128 * 256 + 128 * 128;
 
-__global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
-                                                                    int ld, int d_model, float alpha,
-                                                                    const uint16_t* __restrict__ P,
-                                                                    const uint16_t* __restrict__ dctx, int ld_ctx,
-                                                                    uint16_t* __restrict__ dqkv, int ld_dqkv) {
+// slot (16-byte piece) swizzles: rows of X are 128 bytes (8 pieces), rows of P / dS 256 bytes (16 pieces).  Both make
+// (a) the plain 16-byte fragment reads / stores of 16 consecutive rows at one logical piece and (b) the transposing
+// reads, which touch 4 consecutive rows x 4 consecutive pieces, free of bank conflicts.
+__device__ __forceinline__ int bx_swz(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
+__device__ __forceinline__ int bp_swz(int m) { return ((m & 3) << 2) | ((m >> 2) & 3); }
+
+// Staging of a [rows_valid x 64] matrix into X in two halves, so that the global loads can be requested a phase ahead
+// of the LDS stores: 1024 pieces of 8 columns, 4 per thread, fully coalesced (8 lanes per 128-byte row).
+__device__ __forceinline__ void load_rows_x(const uint16_t* M, int ld, int rows_valid, u32x4a (&r4)[4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int v = threadIdx.x + AT_THREADS * j;
+        r4[j]       = load_row8(M, ld, v >> 3, rows_valid, (v & 7) * 8);
+    }
+}
+__device__ __forceinline__ void store_rows_x(char* X, const u32x4a (&r4)[4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int v = threadIdx.x + AT_THREADS * j;
+        const int r = v >> 3, c = v & 7;
+        *reinterpret_cast<u32x4a*>(X + r * 128 + ((c ^ bx_swz(r)) << 4)) = r4[j];
+    }
+}
+// plain fragment: columns 16 kk + 8 hf ... of row `row` of X
+__device__ __forceinline__ f16x8 x_frag(const char* X, int row, int kk, int hf) {
+    return as_f16x8(*reinterpret_cast<const u32x4a*>(X + row * 128 + (((2 * kk + hf) ^ bx_swz(row)) << 4)));
+}
+typedef short s16x4a __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x2a lds_tr(const char* p) {
+    const s16x4a v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4a*)((__attribute__((address_space(3))) void*)p));
+    return __builtin_bit_cast(u32x2a, v);
+}
+// Transposed fragment of X (matrix rows = contraction index): for output row (column of X) col0 + lane % 32, the 4 + 4
+// contraction indices k_lo .. k_lo + 3 and k_hi .. k_hi + 3.
+__device__ __forceinline__ f16x8 x_frag_t(const char* X, int col0, int k_lo, int k_hi, int lane) {
+    const int i16 = lane & 15, kq = i16 >> 2, c = col0 + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+    const int r0 = k_lo + kq, r1 = k_hi + kq;
+    const u32x2a lo = lds_tr(X + r0 * 128 + (((c >> 3) ^ bx_swz(r0)) << 4) + (c & 4) * 2);
+    const u32x2a hi = lds_tr(X + r1 * 128 + (((c >> 3) ^ bx_swz(r1)) << 4) + (c & 4) * 2);
+    return join_f16x8(lo, hi);
+}
+// The same out of a [128][128] query-major matrix (P or dS): output row = key n0 + lane % 32, contraction over queries.
+__device__ __forceinline__ f16x8 p_frag_t(const char* Pm, int n0, int k_lo, int k_hi, int lane) {
+    const int i16 = lane & 15, kq = i16 >> 2, c = n0 + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+    const int r0 = k_lo + kq, r1 = k_hi + kq;
+    const u32x2a lo = lds_tr(Pm + r0 * 256 + (((c >> 3) ^ bp_swz(r0)) << 4) + (c & 4) * 2);
+    const u32x2a hi = lds_tr(Pm + r1 * 256 + (((c >> 3) ^ bp_swz(r1)) << 4) + (c & 4) * 2);
+    return join_f16x8(lo, hi);
+}
+
+__global__ __launch_bounds__(AT_THREADS, 2) void attention_bwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
+                                                                       int ld, int d_model, float alpha,
+                                                                       const uint16_t* __restrict__ P,
+                                                                       const uint16_t* __restrict__ dctx, int ld_ctx,
+                                                                       uint16_t* __restrict__ dqkv, int ld_dqkv) {
     extern __shared__ __align__(16) char smem[];
-    char* Pt  = smem;
-    char* dSt = Pt + 128 * 256;
-    char* X   = dSt + 128 * 256;
+    char* PS = smem;                 // [128][128] query-major: P for the dV product, then dS for the dK product
+    char* X  = PS + 128 * 256;       // [128][64]: rows of V (dP), dO (dV), K (dQ), Q (dK), one after the other
     const int b = blockIdx.x / n_heads, h = blockIdx.x - b * n_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
     const uint16_t* q  = qkv + (long long)b * S * ld + h * AT_D;
@@ -246,59 +303,140 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
     uint16_t*       dq = dqkv + (long long)b * S * ld_dqkv + h * AT_D;
     uint16_t*       dk = dq + d_model;
     uint16_t*       dv = dq + 2 * d_model;
+    const int       m  = 32 * wave + (lane & 31);
 
-    stage_transposed(k, ld, S, X);  // Kt
-    stage_rows(v, ld, S, Pt);       // the rows of V borrow the start of Pt until dP is done
-    __syncthreads();
-
-    // dP[m][n] = sum_d dctx[m][d] v[n][d], same register layout as the scores (lane <-> query m)
-    f32x16 acc[4];
-    rows_product(Pt, dO, ld_ctx, S, wave, lane, acc);
-    __syncthreads();                // every wave is done with the rows of V before Pt is written
-
-    const int m = 32 * wave + (lane & 31);
-    float     pr[4][16];
-    float     inner = 0.f;
+    // this lane's pieces of its query's probabilities
+    u32x4a pw[4][2];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            // 16 bytes = keys 32t + 16c + 8hf ... of query m; lanes m and m + 32 then trade halves (gather8 is its own
-            // inverse) and hold keys 8q + 4hf + {0..3} for q = 2c (words 0, 1) and q = 2c + 1 (words 2, 3)
-            const int n8 = 32 * t + 16 * c + 8 * hf;
-            u32x4a    w  = u32x4a{0u, 0u, 0u, 0u};
-            if (m < S && n8 < S) w = *reinterpret_cast<const u32x4a*>(Pb + (long long)m * S + n8);
-            w = gather8(w[0], w[1], w[2], w[3]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int r = 8 * c + e;  // = 4 qd + (e % 4) with qd = 2c + e / 4
-                pr[t][r]    = h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu)));
-                const float dp = round16(acc[t][r]);  // dP is a stored tensor
-                acc[t][r]      = dp;
-                inner += dp * pr[t][r];
-            }
+            const int n8 = 32 * t + 16 * c + 8 * hf;  // 16 bytes = keys n8 .. n8 + 7 of query m
+            pw[t][c]     = u32x4a{0u, 0u, 0u, 0u};
+            if (m < S && n8 < S) pw[t][c] = *reinterpret_cast<const u32x4a*>(Pb + (long long)m * S + n8);
         }
-    inner += __shfl_xor(inner, 32, 64);
-    // dS = RNE16(p (dP - inner)); keep it as fp16 pairs, and scatter p and dS transposed into LDS (T[n][m])
-    unsigned ds[4][8];
+    u32x4a ra[4], rb[4];            // the matrix X takes next is requested a phase ahead
+    load_rows_x(v, ld, S, ra);
+    f16x8 bq[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int kk = 0; kk < 4; ++kk) bq[kk] = as_f16x8(load_row8(dO, ld_ctx, m, S, 16 * kk + 8 * hf));
+    load_rows_x(dO, ld_ctx, S, rb);
+    store_rows_x(X, ra);            // rows of V
 #pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-            uint16_t hs[4];
+    for (int t = 0; t < 4; ++t)     // P goes into LDS as it comes from memory (query-major, 16-byte pieces)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int r = 4 * qd + e, n = 32 * t + 8 * qd + 4 * hf + e;
-                hs[e]       = f2h(pr[t][r] * (acc[t][r] - inner));
-                *reinterpret_cast<uint16_t*>(Pt + t128_off(n, m))  = f2h(pr[t][r]);
-                *reinterpret_cast<uint16_t*>(dSt + t128_off(n, m)) = hs[e];
-            }
-            ds[t][2 * qd]     = (unsigned)hs[0] | ((unsigned)hs[1] << 16);
-            ds[t][2 * qd + 1] = (unsigned)hs[2] | ((unsigned)hs[3] << 16);
-        }
-    __syncthreads();  // Kt, Pt, dSt complete
+        for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4a*>(PS + m * 256 + (((4 * t + 2 * c + hf) ^ bp_swz(m)) << 4)) = pw[t][c];
+    __syncthreads();
 
-    // dQ[m][d] = alpha sum_n dS[m][n] k[n][d]: A = Kt rows d (probability-ordered keys), B = dS registers
+    // dP[m][n] = sum_d dctx[m][d] v[n][d], same register layout as the scores (lane <-> query m)
+    f32x16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        acc[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (32 * t < S) {  // wave-uniform
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x_frag(X, 32 * t + (lane & 31), kk, hf), bq[kk], acc[t], 0, 0, 0);
+        }
+    }
+    __syncthreads();                // every wave is done with the rows of V
+    store_rows_x(X, rb);            // the rows of dO
+    load_rows_x(k, ld, S, ra);      // for the dQ product: on their way during the dS arithmetic and the dV product
+
+    // dS = RNE16(p (dP - inner)), inner = sum_n dP p, in registers: lanes m and m + 32 trade halves of their pieces
+    // (gather8 is its own inverse) and hold keys 8 q + 4 hf + {0..3} for q = 2c (words 0, 1) and q = 2c + 1 (words 2, 3)
+    unsigned ds[4][8];
+    {
+        // this lane's own pieces of P come back out of LDS (it wrote them there itself) rather than waiting in registers
+        auto own_p = [&](int t, int c) {
+            const u32x4a w = *reinterpret_cast<const u32x4a*>(PS + m * 256 + (((4 * t + 2 * c + hf) ^ bp_swz(m)) << 4));
+            return gather8(w[0], w[1], w[2], w[3]);
+        };
+        auto prob = [&](const u32x4a& w, int e) { return h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu))); };
+        float inner = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const u32x4a w = own_p(t, c);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int   r  = 8 * c + e;  // = 4 qd + (e % 4) with qd = 2c + e / 4
+                    const float dp = round16(acc[t][r]);  // dP is a stored tensor
+                    acc[t][r]      = dp;
+                    inner += dp * prob(w, e);
+                }
+            }
+        inner += __shfl_xor(inner, 32, 64);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const u32x4a w = own_p(t, c);  // (again: cheaper than keeping 64 floats)
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const int r       = 8 * c + e;
+                    ds[t][4 * c + e / 2] = pack2(prob(w, e) * (acc[t][r] - inner), prob(w, e + 1) * (acc[t][r + 1] - inner));
+                }
+            }
+    }
+    __syncthreads();                // rows of dO (and P) complete
+
+    // The 32 keys n of this wave, contraction over queries m in plain order (8 at 16 kk + 8 hf):
+    //   dV[n][d] = sum_m p[m][n] dctx[m][d]          A = dO^T rows d out of the rows of dO, B = P^T rows n out of P
+    //   dK[n][d] = alpha sum_m dS[m][n] q[m][d]      A = Q^T  rows d out of the rows of Q,  B = dS^T rows n out of dS
+    auto key_product = [&](uint16_t* out, const float scale) {
+        if (32 * wave < S) {  // wave-uniform
+            f32x16 o[2];
+            o[0] = o[1] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            // fragments of slice kk + 1 are requested before the matrix-core work of slice kk, and no further ahead
+            f16x8 fb[2], fa[2][2];
+            auto  fetch = [&](int kk, int buf) {
+                const int m0 = 16 * kk + 8 * hf;  // (rows >= S of P / dS and of X hold zeros)
+                fb[buf]      = p_frag_t(PS, 32 * wave, m0, m0 + 4, lane);
+                fa[buf][0]   = x_frag_t(X, 0, m0, m0 + 4, lane);
+                fa[buf][1]   = x_frag_t(X, 32, m0, m0 + 4, lane);
+            };
+            fetch(0, 0);
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                if (16 * kk < S) {
+                    if (kk + 1 < 8) fetch(kk + 1, (kk + 1) & 1);
+                    o[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[kk & 1][0], fb[kk & 1], o[0], 0, 0, 0);
+                    o[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[kk & 1][1], fb[kk & 1], o[1], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            const int n = 32 * wave + (lane & 31);
+            if (n < S) {
+                uint16_t* row = out + (long long)n * ld_dqkv;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        const int q0 = 8 * c;
+                        *reinterpret_cast<u32x4a*>(row + 32 * dt + 16 * c + 8 * hf) =
+                            gather8(pack2(scale * o[dt][q0], scale * o[dt][q0 + 1]), pack2(scale * o[dt][q0 + 2], scale * o[dt][q0 + 3]),
+                                    pack2(scale * o[dt][q0 + 4], scale * o[dt][q0 + 5]), pack2(scale * o[dt][q0 + 6], scale * o[dt][q0 + 7]));
+                    }
+            }
+        }
+    };
+    key_product(dv, 1.0f);
+
+    __syncthreads();                // every wave is done with P and the rows of dO
+    store_rows_x(X, ra);            // the rows of K
+#pragma unroll
+    for (int t = 0; t < 4; ++t)     // dS over P, traded back into 8 consecutive keys per lane
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            *reinterpret_cast<u32x4a*>(PS + m * 256 + (((4 * t + 2 * c + hf) ^ bp_swz(m)) << 4)) =
+                gather8(ds[t][4 * c], ds[t][4 * c + 1], ds[t][4 * c + 2], ds[t][4 * c + 3]);
+    load_rows_x(q, ld, S, rb);      // for the dK product: on their way during the dQ product
+    __syncthreads();                // rows of K and dS complete
+
+    // dQ[m][d] = alpha sum_n dS[m][n] k[n][d]: A = K^T rows d out of the rows of K (keys in the registers' order: 4 at
+    // 32 t + 16 s + 4 hf and 4 more 8 further), B = dS registers
     {
         f32x16 o[2];
 #pragma unroll
@@ -310,8 +448,8 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
 #pragma unroll
                     for (int s = 0; s < 2; ++s) {
                         const f16x8 dsf = as_f16x8(u32x4a{ds[t][4 * s], ds[t][4 * s + 1], ds[t][4 * s + 2], ds[t][4 * s + 3]});
-                        const f16x8 kt  = t128_frag_pairs(X, 32 * dt + (lane & 31), t, s, hf);
-                        o[dt]           = __builtin_amdgcn_mfma_f32_32x32x16_f16(kt, dsf, o[dt], 0, 0, 0);
+                        const int   n0  = 32 * t + 16 * s + 4 * hf;
+                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x_frag_t(X, 32 * dt, n0, n0 + 8, lane), dsf, o[dt], 0, 0, 0);
                     }
                 }
             }
@@ -329,45 +467,10 @@ __global__ __launch_bounds__(AT_THREADS) void attention_bwd_kernel(int n_heads, 
                 }
         }
     }
-    // dV[n][d] = sum_m p[m][n] dctx[m][d] and dK[n][d] = alpha sum_m dS[m][n] q[m][d] for the 32 keys n of this wave:
-    // A = dOt / Qt rows d, B = Pt / dSt rows n, contraction over queries m in plain order.
-    const int n = 32 * wave + (lane & 31);
-#pragma unroll
-    for (int which = 0; which < 2; ++which) {
-        __syncthreads();  // everyone is done reading X
-        stage_transposed(which == 0 ? dO : q, which == 0 ? ld_ctx : ld, S, X);  // dOt, then Qt
-        __syncthreads();
-        if (32 * wave < S) {  // wave-uniform
-            const char* Bt    = which == 0 ? Pt : dSt;
-            uint16_t*   out   = which == 0 ? dv : dk;
-            const float scale = which == 0 ? 1.0f : alpha;
-            f32x16      o[2];
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                o[dt] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    if (16 * kk < S) {
-                        const f16x8 a  = t128_frag(X, 32 * dt + (lane & 31), kk, hf);
-                        const f16x8 bb = t128_frag(Bt, n, kk, hf);
-                        o[dt]          = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bb, o[dt], 0, 0, 0);
-                    }
-                }
-            }
-            if (n < S) {
-                uint16_t* row = out + (long long)n * ld_dqkv;
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                    for (int c = 0; c < 2; ++c) {
-                        const int q0 = 8 * c;
-                        *reinterpret_cast<u32x4a*>(row + 32 * dt + 16 * c + 8 * hf) =
-                            gather8(pack2(scale * o[dt][q0], scale * o[dt][q0 + 1]), pack2(scale * o[dt][q0 + 2], scale * o[dt][q0 + 3]),
-                                    pack2(scale * o[dt][q0 + 4], scale * o[dt][q0 + 5]), pack2(scale * o[dt][q0 + 6], scale * o[dt][q0 + 7]));
-                    }
-            }
-        }
-    }
+    __syncthreads();                // every wave is done with the rows of K
+    store_rows_x(X, rb);            // the rows of Q
+    __syncthreads();
+    key_product(dk, alpha);
 }
 
 }  // namespace mp
