@@ -55,186 +55,11 @@ __device__ __forceinline__ u32x4a load_row8(const uint16_t* base, int ld, int ro
     return u32x4a{0u, 0u, 0u, 0u};
 }
 
-// LDS matrix T[R rows][128 halves] (256-byte rows, 16 slots of 16 bytes), slot index XOR (row & 15) so that 16
-// consecutive rows read the same logical slot from 16 different bank groups.
-__device__ __forceinline__ int t128_off(int row, int col) {  // byte offset of element (row, col)
-    return row * 256 + ((((col >> 3) ^ row) & 15) << 4) + (col & 7) * 2;
-}
-
-// Transposing store: the workgroup copies a [rows_valid x 64] fp16 matrix M (row-major, leading dimension ld)
-// into T[64][128] with T[c][r] = M[r][c]; rows >= rows_valid become zero.
-__device__ __forceinline__ void stage_transposed(const uint16_t* M, int ld, int rows_valid, char* T) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int v = threadIdx.x + AT_THREADS * j;  // 1024 vectors of 8 columns
-        const int r = v >> 3, c0 = (v & 7) * 8;
-        const u32x4a q = load_row8(M, ld, r, rows_valid, c0);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const unsigned w = q[e >> 1];
-            *reinterpret_cast<uint16_t*>(T + t128_off(c0 + e, r)) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
-        }
-    }
-}
-
-// Fragment of T for the "probability-ordered" k-set of (tile t, half-slice s): row = lane%32 (+ row0).
-__device__ __forceinline__ f16x8 t128_frag_pairs(const char* T, int row, int t, int s, int hf) {
-    const int     c  = 32 * t + 16 * s + 4 * hf;
-    const u32x2a  lo = *reinterpret_cast<const u32x2a*>(T + t128_off(row, c));
-    const u32x2a  hi = *reinterpret_cast<const u32x2a*>(T + t128_off(row, c + 8));
-    return join_f16x8(lo, hi);
-}
-// Fragment of T with 8 consecutive columns starting at 16 kk + 8 hf (the plain k-order).
-__device__ __forceinline__ f16x8 t128_frag(const char* T, int row, int kk, int hf) {
-    return as_f16x8(*reinterpret_cast<const u32x4a*>(T + t128_off(row, 16 * kk + 8 * hf)));
-}
-
-// Row-major staging: the workgroup copies a [rows_valid x 64] fp16 matrix M into LDS rows of 128 bytes (8 slots of 16
-// bytes, slot index XOR a function of the row, so that 32 consecutive rows read one logical slot without bank
-// conflicts); rows >= rows_valid become zero.  Loads are fully coalesced (8 lanes per 128-byte row), which the
-// matrix-core fragments (16 bytes of 32 different rows per instruction) are not: fetched straight from global memory
-// every fragment costs one cache access per 32 bytes, and every wave fetches the whole matrix again.
-__device__ __forceinline__ int r64_swz(int row) { return (row ^ (row >> 3)) & 7; }
-__device__ __forceinline__ void stage_rows(const uint16_t* M, int ld, int rows_valid, char* R) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int v = threadIdx.x + AT_THREADS * j;  // 1024 vectors of 8 columns
-        const int r = v >> 3, c = v & 7;
-        *reinterpret_cast<u32x4a*>(R + r * 128 + ((c ^ r64_swz(r)) << 4)) = load_row8(M, ld, r, rows_valid, c * 8);
-    }
-}
-// 8 consecutive columns 16 kk + 8 hf ... of staged row `row`
-__device__ __forceinline__ f16x8 rows_frag(const char* R, int row, int kk, int hf) {
-    return as_f16x8(*reinterpret_cast<const u32x4a*>(R + row * 128 + (((2 * kk + hf) ^ r64_swz(row)) << 4)));
-}
-
-// scores / dP tile product for one wave: D[n][m] = sum_d Arows[n][d] * Brows[m][d]; the key-side operand A (all 128
-// rows, used by every wave) comes from its staged copy in LDS, the query-side operand B (this wave's 32 rows, used
-// once) straight from global memory; m = 32 wave + lane%32, n over four 32-key tiles.
-__device__ __forceinline__ void rows_product(const char* An_lds, const uint16_t* Bm, int ldb, int S, int wave, int lane,
-                                             f32x16 (&acc)[4]) {
-    const int hf = lane >> 5, m = 32 * wave + (lane & 31);
-    f16x8     bq[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) bq[kk] = as_f16x8(load_row8(Bm, ldb, m, S, 16 * kk + 8 * hf));
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        acc[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (32 * t < S) {  // wave-uniform
-            const int n = 32 * t + (lane & 31);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rows_frag(An_lds, n, kk, hf), bq[kk], acc[t], 0, 0, 0);
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------------ forward
-__global__ __launch_bounds__(AT_THREADS, 4) void attention_fwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
-                                                                    int ld, int d_model, float alpha,
-                                                                    uint16_t* __restrict__ P, uint16_t* __restrict__ ctx,
-                                                                    int ld_ctx) {
-    extern __shared__ __align__(16) char smem[];  // Vt[64][128] (16 KB), then the rows of K (16 KB)
-    char* Krows = smem + 64 * 256;
-    const int b = blockIdx.x / n_heads, h = blockIdx.x - b * n_heads;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
-    const uint16_t* q = qkv + (long long)b * S * ld + h * AT_D;
-    const uint16_t* k = q + d_model;
-    const uint16_t* v = q + 2 * d_model;
-    uint16_t*       Pb = P + (long long)blockIdx.x * S * S;
-
-    stage_rows(k, ld, S, Krows);
-    stage_transposed(v, ld, S, smem);  // Vt[d][n]
-    __syncthreads();                   // K rows (and Vt) complete
-
-    f32x16 acc[4];
-    rows_product(Krows, q, ld, S, wave, lane, acc);
-
-    // softmax over the keys of query m; a lane holds 64 of its 128 scores, lane^32 the others
-    const int m  = 32 * wave + (lane & 31);
-    float     mx = -INFINITY;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int   n = 32 * t + 8 * (r >> 2) + 4 * hf + (r & 3);
-            const float s = (n < S) ? round16(alpha * acc[t][r]) : -INFINITY;
-            acc[t][r]     = s;
-            mx            = fmaxf(mx, s);
-        }
-    mx        = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float sum = 0.f;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float e = __expf(acc[t][r] - mx);  // exp(-inf) = 0 for masked keys
-            acc[t][r]     = e;
-            sum += e;
-        }
-    sum += __shfl_xor(sum, 32, 64);
-    const float inv = 1.0f / sum;  // one division per query (the kernel is bound by vector ALU work); e * inv is within
-                                   // one fp32 ulp of e / sum, far inside the rounding to fp16 that follows
-    unsigned pk[4][8];  // probabilities as fp16 pairs: pk[t][2q], pk[t][2q+1] = keys 32t + 8q + 4hf + {0,1},{2,3}
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-            pk[t][2 * qd]     = pack2(acc[t][4 * qd] * inv, acc[t][4 * qd + 1] * inv);
-            pk[t][2 * qd + 1] = pack2(acc[t][4 * qd + 2] * inv, acc[t][4 * qd + 3] * inv);
-        }
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const u32x4a row8 = gather8(pk[t][4 * c], pk[t][4 * c + 1], pk[t][4 * c + 2], pk[t][4 * c + 3]);
-            const int    n    = 32 * t + 16 * c + 8 * hf;  // (S is a multiple of 8: a piece is inside or outside as a whole)
-            if (m < S && n < S) *reinterpret_cast<u32x4a*>(Pb + (long long)m * S + n) = row8;
-        }
-    }
-
-    // ctx[m][d] = sum_n p[m][n] v[n][d]: A = Vt rows d, B = probability registers
-    f32x16 o[2];
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt) {
-        o[dt] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            if (32 * t < S) {
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const f16x8 pv = as_f16x8(u32x4a{pk[t][4 * s], pk[t][4 * s + 1], pk[t][4 * s + 2], pk[t][4 * s + 3]});
-                    const f16x8 vt = t128_frag_pairs(smem, 32 * dt + (lane & 31), t, s, hf);
-                    o[dt]          = __builtin_amdgcn_mfma_f32_32x32x16_f16(vt, pv, o[dt], 0, 0, 0);
-                }
-            }
-        }
-    }
-    if (m < S) {
-        uint16_t* crow = ctx + ((long long)b * S + m) * ld_ctx + h * AT_D;
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const int q0 = 8 * c;  // accumulator registers of the column groups q = 2c, 2c + 1
-                *reinterpret_cast<u32x4a*>(crow + 32 * dt + 16 * c + 8 * hf) =
-                    gather8(pack2(o[dt][q0], o[dt][q0 + 1]), pack2(o[dt][q0 + 2], o[dt][q0 + 3]),
-                            pack2(o[dt][q0 + 4], o[dt][q0 + 5]), pack2(o[dt][q0 + 6], o[dt][q0 + 7]));
-            }
-    }
-}
-
-// ------------------------------------------------------------------------------------ backward
-// Every matrix sits in LDS the way it sits in memory (row-major, staged with coalesced 16-byte accesses); whatever a
-// product needs transposed comes out of the transposing LDS read (`ds_read_b64_tr_b16`: within 16 lanes, the four
-// lanes 4 j .. 4 j + 3 address 8-byte chunks of matrix row k0 + j covering 16 consecutive columns, and lane i gets
-// column i of rows k0 .. k0 + 3), two reads per 8-deep matrix-core fragment.  No 2-byte LDS scatters, no transposing
-// stagings.
-// LDS: one [128][128] query-major buffer (32 KB) that holds P for the dV product and then dS for the dK product, plus one
-// [128][64] buffer X (16 KB) that holds the rows of V (dP), dO (dV), K (dQ) and Q (dK) in turn: 48 KiB; the matrix that
-// X takes next is always already on its way from memory in registers.  Two workgroups share a CU: the registers, not
-// the LDS, set that (a third workgroup per CU would leave 168 registers per lane, and the spills that costs took the
-// kernel from 36 to 65 us per layer).
-constexpr int AT_BWD_LDS = 128 * 256 + 128 * 128;
-
+// ------------------------------------------------------------------------------------ row-major LDS + transposing reads
+// Matrices sit in LDS the way they sit in memory (row-major, staged with coalesced 16-byte accesses); whatever a product
+// needs transposed comes out of the transposing LDS read (`ds_read_b64_tr_b16`: within 16 lanes, the four lanes
+// 4 j .. 4 j + 3 address 8-byte chunks of matrix row k0 + j covering 16 consecutive columns, and lane i gets column i
+// of rows k0 .. k0 + 3), two reads per 8-deep matrix-core fragment.
 // slot (16-byte piece) swizzles: rows of X are 128 bytes (8 pieces), rows of P / dS 256 bytes (16 pieces).  Both make
 // (a) the plain 16-byte fragment reads / stores of 16 consecutive rows at one logical piece and (b) the transposing
 // reads, which touch 4 consecutive rows x 4 consecutive pieces, free of bank conflicts.
@@ -284,6 +109,139 @@ __device__ __forceinline__ f16x8 p_frag_t(const char* Pm, int n0, int k_lo, int 
     const u32x2a hi = lds_tr(Pm + r1 * 256 + (((c >> 3) ^ bp_swz(r1)) << 4) + (c & 4) * 2);
     return join_f16x8(lo, hi);
 }
+
+// scores / dP tile product for one wave: D[n][m] = sum_d Arows[n][d] * Brows[m][d]; the key-side operand A (all 128
+// rows, used by every wave) comes from its staged copy in LDS (plain fragments: the contraction index is the
+// column), the query-side operand B (this wave's 32 rows, used once) straight from global memory;
+// m = 32 wave + lane % 32, n over four 32-key tiles.
+__device__ __forceinline__ void rows_product(const char* An_lds, const uint16_t* Bm, int ldb, int S, int wave, int lane,
+                                             f32x16 (&acc)[4]) {
+    const int hf = lane >> 5, m = 32 * wave + (lane & 31);
+    f16x8     bq[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) bq[kk] = as_f16x8(load_row8(Bm, ldb, m, S, 16 * kk + 8 * hf));
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        acc[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (32 * t < S) {  // wave-uniform
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x_frag(An_lds, 32 * t + (lane & 31), kk, hf), bq[kk], acc[t], 0, 0, 0);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------ forward
+__global__ __launch_bounds__(AT_THREADS, 4) void attention_fwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
+                                                                    int ld, int d_model, float alpha,
+                                                                    uint16_t* __restrict__ P, uint16_t* __restrict__ ctx,
+                                                                    int ld_ctx) {
+    extern __shared__ __align__(16) char smem[];  // the rows of V (16 KB), then the rows of K (16 KB)
+    char* Krows = smem + 128 * 128;
+    const int b = blockIdx.x / n_heads, h = blockIdx.x - b * n_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
+    const uint16_t* q = qkv + (long long)b * S * ld + h * AT_D;
+    const uint16_t* k = q + d_model;
+    const uint16_t* v = q + 2 * d_model;
+    uint16_t*       Pb = P + (long long)blockIdx.x * S * S;
+
+    {
+        u32x4a rk[4], rv[4];
+        load_rows_x(k, ld, S, rk);
+        load_rows_x(v, ld, S, rv);
+        store_rows_x(Krows, rk);
+        store_rows_x(smem, rv);
+    }
+    __syncthreads();                   // rows of K and V complete
+
+    f32x16 acc[4];
+    rows_product(Krows, q, ld, S, wave, lane, acc);
+
+    // softmax over the keys of query m; a lane holds 64 of its 128 scores, lane^32 the others
+    const int m  = 32 * wave + (lane & 31);
+    float     mx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int   n = 32 * t + 8 * (r >> 2) + 4 * hf + (r & 3);
+            const float s = (n < S) ? round16(alpha * acc[t][r]) : -INFINITY;
+            acc[t][r]     = s;
+            mx            = fmaxf(mx, s);
+        }
+    mx        = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float e = __expf(acc[t][r] - mx);  // exp(-inf) = 0 for masked keys
+            acc[t][r]     = e;
+            sum += e;
+        }
+    sum += __shfl_xor(sum, 32, 64);
+    const float inv = 1.0f / sum;  // one division per query (the kernel is bound by vector ALU work); e * inv is within
+                                   // one fp32 ulp of e / sum, far inside the rounding to fp16 that follows
+    unsigned pk[4][8];  // probabilities as fp16 pairs: pk[t][2q], pk[t][2q+1] = keys 32t + 8q + 4hf + {0,1},{2,3}
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            pk[t][2 * qd]     = pack2(acc[t][4 * qd] * inv, acc[t][4 * qd + 1] * inv);
+            pk[t][2 * qd + 1] = pack2(acc[t][4 * qd + 2] * inv, acc[t][4 * qd + 3] * inv);
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const u32x4a row8 = gather8(pk[t][4 * c], pk[t][4 * c + 1], pk[t][4 * c + 2], pk[t][4 * c + 3]);
+            const int    n    = 32 * t + 16 * c + 8 * hf;  // (S is a multiple of 8: a piece is inside or outside as a whole)
+            if (m < S && n < S) *reinterpret_cast<u32x4a*>(Pb + (long long)m * S + n) = row8;
+        }
+    }
+
+    // ctx[m][d] = sum_n p[m][n] v[n][d]: A = V^T rows d out of the rows of V, B = probability registers
+    f32x16 o[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) {
+        o[dt] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (32 * t < S) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const f16x8 pv = as_f16x8(u32x4a{pk[t][4 * s], pk[t][4 * s + 1], pk[t][4 * s + 2], pk[t][4 * s + 3]});
+                    const int   n0 = 32 * t + 16 * s + 4 * hf;  // the registers' key order: 4 keys here, 4 more 8 further
+                    const f16x8 vt = x_frag_t(smem, 32 * dt, n0, n0 + 8, lane);
+                    o[dt]          = __builtin_amdgcn_mfma_f32_32x32x16_f16(vt, pv, o[dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (m < S) {
+        uint16_t* crow = ctx + ((long long)b * S + m) * ld_ctx + h * AT_D;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int q0 = 8 * c;  // accumulator registers of the column groups q = 2c, 2c + 1
+                *reinterpret_cast<u32x4a*>(crow + 32 * dt + 16 * c + 8 * hf) =
+                    gather8(pack2(o[dt][q0], o[dt][q0 + 1]), pack2(o[dt][q0 + 2], o[dt][q0 + 3]),
+                            pack2(o[dt][q0 + 4], o[dt][q0 + 5]), pack2(o[dt][q0 + 6], o[dt][q0 + 7]));
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------ backward
+// Every matrix sits in LDS the way it sits in memory (row-major, staged with coalesced 16-byte accesses); whatever a
+// product needs transposed comes out of the transposing LDS read (`ds_read_b64_tr_b16`: within 16 lanes, the four
+// lanes 4 j .. 4 j + 3 address 8-byte chunks of matrix row k0 + j covering 16 consecutive columns, and lane i gets
+// column i of rows k0 .. k0 + 3), two reads per 8-deep matrix-core fragment.  No 2-byte LDS scatters, no transposing
+// stagings.
+// LDS: one [128][128] query-major buffer (32 KB) that holds P for the dV product and then dS for the dK product, plus one
+// [128][64] buffer X (16 KB) that holds the rows of V (dP), dO (dV), K (dQ) and Q (dK) in turn: 48 KiB; the matrix that
+// X takes next is always already on its way from memory in registers.  Two workgroups share a CU: the registers, not
+// the LDS, set that (a third workgroup per CU would leave 168 registers per lane, and the spills that costs took the
+// kernel from 36 to 65 us per layer).
+constexpr int AT_BWD_LDS = 128 * 256 + 128 * 128;
 
 __global__ __launch_bounds__(AT_THREADS, 2) void attention_bwd_kernel(int n_heads, int S, const uint16_t* __restrict__ qkv,
                                                                        int ld, int d_model, float alpha,
