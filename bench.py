@@ -27,11 +27,23 @@ sys.path.insert(0, ROOT)
 PEAK_FP16_TFLOPS = 2500.0   # MI355X dense fp16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per launch from the rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE, each scaled by
-# what the same counter reads for the 256 MiB calibration copy below); the summaries with the commands are
-# profiles/gemm_update_config3_hbm_traffic.txt.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 170050219       # fetch 137.4 MB + write 32.6 MB, average over the launches of a step
-UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 2116335436    # fetch 1058.3 MB + write 1058.1 MB
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "gemm_update_config3_hbm_traffic.txt")
+
+
+def traffic_from_summary():
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB copy) as
+    the last counter runs of this script left them in profiles/ (written by `python -m paper_1805_10387_amd.profile_summary
+    traffic ...`, whose command lines are in that file).  None when the summary is missing: the value is never typed in."""
+    out = {"gemm": None, "update": None}
+    try:
+        for line in open(TRAFFIC_SUMMARY):
+            for key in out:
+                tag = f"{key}_traffic_bytes_per_launch ="
+                if line.strip().startswith(tag):
+                    out[key] = int(float(line.split("=")[1].split()[0]))
+    except OSError:
+        pass
+    return out
 
 
 def _time_calls(torch, fn, reps):
@@ -129,41 +141,131 @@ class GemmTimer:
         return len(self.rec), sum(r[2] for r in self.rec), sum(r[3] for r in self.rec), raw, empty
 
 
-def cpu_baseline(wl, seconds_hint=20.0):
-    """The oracle, as it stands, on a bounded sample of config 3: all 6 layers at full width, 16 of the 64
-    sequences (2048 of 8192 tokens), complete iterations (forward, loss, backward, Adam on masters)."""
-    import numpy as np
-    from threadpoolctl import threadpool_info
+def _host_cores():
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def _time_oracle(wl, iterations, threads=None):
+    """Seconds per complete oracle iteration (forward, loss, backward, Adam on masters) of a Transformer workload."""
+    from threadpoolctl import threadpool_info, threadpool_limits
     from oracle import MIXED
     from oracle import models as Mo
-    sample = replace(wl, n_seq=16)
-    masters = Mo.flatten_layers(sample.masters())
-    tr = Mo.Trainer(MIXED, masters, sample.opt, sample.scale)
-    f = Mo.make_transformer_fwd_bwd(sample.n_layers, sample.n_seq, sample.seq_len, sample.n_heads)
-    batch = Mo.island_batch(MIXED, sample.batch())
+    masters = Mo.flatten_layers(wl.masters())
+    tr = Mo.Trainer(MIXED, masters, wl.opt, wl.scale)
+    f = Mo.make_transformer_fwd_bwd(wl.n_layers, wl.n_seq, wl.seq_len, wl.n_heads)
+    batch = Mo.island_batch(MIXED, wl.batch())
     times = []
-    t_start = time.perf_counter()
-    while len(times) < 2 or (time.perf_counter() - t_start < seconds_hint and len(times) < 6):
-        t0 = time.perf_counter()
-        tr.step(f, batch)
-        times.append(time.perf_counter() - t0)
-    best = min(times)
-    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    return {"value": sample.tokens / best, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{sample.n_layers} layers x {sample.n_seq} of {wl.n_seq} sequences ({sample.tokens} tokens), "
-                      f"{len(times)} full iterations, best {best:.2f} s/iteration"}
+    ctx = threadpool_limits(limits=threads) if threads else None
+    try:
+        for _ in range(iterations):
+            t0 = time.perf_counter()
+            tr.step(f, batch)
+            times.append(time.perf_counter() - t0)
+        used = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    finally:
+        if ctx is not None:
+            ctx.restore_original_limits()
+    return min(times), times, int(used)
+
+
+def cpu_baseline(wl, c2, iterations=2):
+    """The oracle, as it stands, on the FULL config-3 workload (6 layers, all 64 sequences = 8192 tokens): complete
+    iterations, best of `iterations`; plus one single-thread figure on config 2 (one layer, 4096 tokens)."""
+    best, times, used = _time_oracle(wl, iterations)
+    c2_best, c2_times, _ = _time_oracle(c2, 2, threads=1)
+    return {"value": wl.tokens / best, "unit": "tokens/s", "cores": used, "host_cores": _host_cores(), "kind": "oracle",
+            "blas_threads": used,
+            "sample": f"full workload: {wl.n_layers} layers x {wl.n_seq} sequences x {wl.seq_len} tokens, {len(times)} complete "
+                      f"iterations ({', '.join(f'{t:.1f}' for t in times)} s), best {best:.2f} s/iteration; NumPy with its BLAS on "
+                      f"{used} threads of {_host_cores()} host cores",
+            "config2_single_core": {"value": c2.tokens / c2_best, "unit": "tokens/s", "cores": 1,
+                                    "sample": f"config 2 (1 layer, {c2.tokens} tokens), 2 complete iterations, best {c2_best:.2f} s"}}
+
+
+def glue_roofline(torch, B, step, I):
+    """The bandwidth-bound kernels of the step, each alone and back to back on its own buffers: algorithmic bytes (every
+    stored tensor read / written once) over time, against 8 TB/s."""
+    wl, a, w = step.wl, step.act[0], step.P.w16
+    T, d, h, S, NB = wl.tokens, wl.d_model, wl.n_heads, wl.seq_len, wl.n_seq
+    tb = step.tmp[0]
+    st = step.st
+    e2 = 2.0  # bytes per fp16 element
+    P_bytes = NB * h * S * S * e2
+    calls = {
+        "attention_fwd": (T * 3 * d * e2 + P_bytes + T * d * e2,
+                          lambda: B.mp_attention_fwd(NB, h, S, d // h, a["qkv"], 3 * d, step.alpha, a["p"], a["ctx"], d)),
+        "attention_bwd": (T * 3 * d * e2 + P_bytes + T * d * e2 + T * 3 * d * e2,
+                          lambda: B.mp_attention_bwd(NB, h, S, d // h, a["qkv"], 3 * d, step.alpha, a["p"], step.dctx, d, tb["dqkv"], 3 * d)),
+        "layernorm_fwd": (3 * T * d * e2 + 8.0 * T,
+                          lambda: B.mp_layernorm_fwd(T, d, step.x0, a["a"], w["l0.ln1_g"], w["l0.ln1_b"], 1e-5, a["y1"], a["mean1"], a["rstd1"])),
+        "layernorm_bwd": (4 * T * d * e2 + 8.0 * T,
+                          lambda: B.mp_layernorm_bwd(T, d, step.dy1, step.x0, a["a"], w["l0.ln1_g"], a["mean1"], a["rstd1"], tb["dz1"],
+                                                     step.P.g16["l0.ln1_g"], step.P.g16["l0.ln1_b"], st, step.ws, dz_colsum=step.P.g16["l0.bo"])),
+    }
+    # softmax cross-entropy at config 4's size (8192 x 32768 logits, in place): not part of this step, timed for the record
+    c4 = I.C4
+    logits = torch.randn(c4.tokens, c4.vocab, device="cuda", dtype=torch.float16)
+    targets = torch.randint(0, c4.vocab, (c4.tokens,), device="cuda", dtype=torch.int32)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.mp_loss_workspace_bytes(c4.tokens, c4.vocab) // 4 + 64, dtype=torch.float32, device="cuda")
+    calls["softmax_xent (config 4 size)"] = (2.0 * c4.tokens * c4.vocab * e2,
+                                             lambda: B.mp_softmax_xent_scaled(c4.tokens, c4.vocab, logits, c4.vocab, targets, st, loss, logits, ws))
+    out = {}
+    for name, (nbytes, fn) in calls.items():
+        t = _time_calls(torch, fn, 20)
+        out[name] = {"bytes": nbytes, "us": round(t * 1e6, 2), "GB/s": round(nbytes / t * 1e-9, 1),
+                     "frac": round(nbytes / t * 1e-9 / PEAK_HBM_GBS, 3)}
+    del logits
+    return out
+
+
+def sclk_under_load(torch, run, seconds=1.5):
+    """Shader clock (MHz) that rocm-smi reports while the step replays: the chip lowers it under matrix-core load
+    according to the power the operand values draw, which moves the real ceiling below the datasheet peak."""
+    import json as _json
+    import subprocess
+    import threading
+    vals, stop = [], [False]
+
+    def sampler():
+        while not stop[0]:
+            try:
+                o = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=5).stdout
+                c = _json.loads(o)["card0"]
+                for k, v in c.items():
+                    if k.startswith("sclk clock speed"):
+                        vals.append(int("".join(ch for ch in v if ch.isdigit())))
+            except Exception:
+                return
+            time.sleep(0.1)
+
+    th = threading.Thread(target=sampler)
+    th.start()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            run()
+        torch.cuda.synchronize()
+    stop[0] = True
+    th.join()
+    vals = sorted(vals[1:]) if len(vals) > 2 else sorted(vals)
+    return vals[len(vals) // 2] if vals else None
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--steps", type=int, default=120, help="timed steps per repeat")
+    ap.add_argument("--repeats", type=int, default=5, help="timed repeats of --steps steps; the median is reported")
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
     ap.add_argument("--one-stream", action="store_true",
                     help="keep the weight-gradient launch and the bias-gradient column sums on the main stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--cpu-iterations", type=int, default=2, help="complete oracle iterations of the full workload")
     ap.add_argument("--insitu-steps", type=int, default=3, help="eager steps whose contractions are timed one by one")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -194,14 +296,21 @@ def main():
         run = graph.replay
         run()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
-        run()
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    # timing protocol: `repeats` times exactly `steps` steps between two events on the stream, no host sync inside;
+    # the median repeat is the figure, all repeats are reported
+    rep_ms = []
+    for _ in range(max(args.repeats, 1)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        rep_ms.append(e0.elapsed_time(e1) / args.steps)
+    ms_per_step = sorted(rep_ms)[len(rep_ms) // 2]
     tokens_per_s = wl.tokens / (ms_per_step * 1e-3)
+    sclk = sclk_under_load(torch, run) if not args.no_graph else None
     st = step.state()
     loss = float(step.loss)
 
@@ -218,6 +327,8 @@ def main():
     secs = raw_secs - empty_secs                  # bracket minus empty bracket = the launches themselves
     # the 12 distinct contractions of one layer again, each alone and back to back (operands warm in L2)
     iso_flops, iso_secs, per = gemm_roofline(torch, B, step)
+    glue = glue_roofline(torch, B, step, I)
+    traffic = traffic_from_summary()
     n_params = step.P.total                       # elements the flat update descriptor covers
     upd_bytes = 28.0 * n_params
     t_upd = _time_calls(torch, lambda: B.mp_unscale_check_update(step.P.flat_list, 1, step.cfg, step.st, 1), 10)
@@ -242,7 +353,9 @@ def main():
     out = {
         "metric": "training tokens/sec (fp16 MP step, Transformer-big layer); MFMA util %",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "repeats": len(rep_ms), "ms_per_step_repeats": [round(t, 4) for t in rep_ms],
+        "spread_pct": round(100.0 * (max(rep_ms) - min(rep_ms)) / ms_per_step, 2),
+        "timing": f"median of {len(rep_ms)} repeats of {args.steps} steps each (HIP events on the stream, no host sync inside)", "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": "config 3: Transformer-big stack, 6 layers, d_model 1024, 16 heads, d_ff 4096, "
                                "64 sequences x 128 tokens = 8192 tokens, fp16 with fp32 masters, MSE, Adam, "
@@ -253,26 +366,30 @@ def main():
         "step_gemm_tflops": wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12,
         "step_mfma_util_pct": 100.0 * wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12 / PEAK_FP16_TFLOPS,
         "final_loss": loss, "loss_scale": st.scale, "opt_steps": st.opt_step, "skipped": st.skipped_steps,
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel / gemm_grouped_kernel (every dense fp16 contraction of the step: per layer 4 fwd, 4 dX, and the 4 dW in one grouped launch)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel / gemm_dtl_grouped_kernel (every dense fp16 contraction of the step: per layer 4 fwd, 4 dX, and the 4 dW in one grouped launch)",
                      "achieved": flops / secs * 1e-12, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / secs * 1e-12 / PEAK_FP16_TFLOPS,
-                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+                     "traffic": traffic["gemm"],
                      "launches_timed": n_launch, "launches_per_step": n_launch // max(args.insitu_steps, 1),
                      "avg_launch_us": secs / n_launch * 1e6, "avg_bracket_us": raw_secs / n_launch * 1e6,
                      "avg_empty_bracket_us": empty_secs / n_launch * 1e6, "flops_per_launch": flops / n_launch,
                      "algorithmic_bytes_per_launch": gemm_bytes / n_launch,
                      "isolated": {"achieved": iso_flops / iso_secs * 1e-12, "per_call": per},
                      "sustained_mfma_tflops": mfma_rate,
+                     "sclk_mhz_under_load": sclk, "sclk_mhz_max": 2400,
+                     "peak_at_sclk_under_load": (PEAK_FP16_TFLOPS * sclk / 2400.0) if sclk else None,
+                     "frac_of_peak_at_sclk_under_load": (flops / secs * 1e-12 / (PEAK_FP16_TFLOPS * sclk / 2400.0)) if sclk else None,
                      "frac_of_sustained_normal_operands": flops / secs * 1e-12 / mfma_rate["normal_operands"]},
         "roofline_update": {"bound": "hbm", "kernel": "update_kernel<ADAM> (unscale + Adam + fp16 re-cast)",
                             "achieved": upd_bytes / t_upd * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                            "frac": upd_bytes / t_upd * 1e-9 / PEAK_HBM_GBS, "traffic": UPDATE_TRAFFIC_BYTES_PER_LAUNCH,
+                            "frac": upd_bytes / t_upd * 1e-9 / PEAK_HBM_GBS, "traffic": traffic["update"],
                             "bytes_per_launch": upd_bytes, "us": t_upd * 1e6,
                             "with_inspection_pass_us": t_upd_chk * 1e6,
                             "with_inspection_pass_GBs": (upd_bytes + 2.0 * n_params) / t_upd_chk * 1e-9},
     }
+    out["roofline_glue"] = glue
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(wl, I.C2, args.cpu_iterations)
     print(json.dumps(out))
 
 
