@@ -71,10 +71,10 @@ def traffic(a):
         for k in sorted(tot, key=lambda x: -tot[x])[:16]:
             out.append(f"{k:<80}{cnt[k]:>11}{tot[k]:>16.1f}{tot[k] / cnt[k]:>15.1f}")
         out.append("")
-        cal = max(grids.values(), key=lambda v: v[0]) if grids else None     # the 256 MiB copy has the largest grid
+        cal = max(grids.values(), key=lambda v: (v[0], v[1])) if grids else None   # the 256 MiB copy: largest grid, most bytes
         factor[counter] = (262144.0 / cal[1]) if cal and cal[1] > 0 else 1.0
         res[counter] = (tot, cnt)
-    out.append("calibration (__amd_rocclr_copyBuffer with the largest grid: the 256 MiB copy, 262144 KiB read and written):")
+    out.append("calibration (the __amd_rocclr_copyBuffer dispatch with the largest grid and reading: the 256 MiB copy, 262144 KiB read and written):")
     out.append(f"  FETCH_SIZE factor {factor['FETCH_SIZE']:.4f}   WRITE_SIZE factor {factor['WRITE_SIZE']:.4f}")
     out.append("")
 
