@@ -108,3 +108,39 @@ def test_overflow_becomes_inf_not_saturation():
     x = MIXED.store(np.full((1, 64), 200.0))
     w = MIXED.store(np.full((1, 64), 200.0))
     assert L.linear_fwd(MIXED, x, w)[0, 0] == np.inf       # 64 * 4e4 > 65504
+
+
+def test_library_matmul_step_against_the_plain_ascending_k_contraction():
+    """The oracle's contractions are NumPy matmuls (a BLAS routine that blocks and orders the fp32 sum as it likes).
+    Section 3.1 only fixes "half-precision operands, single-precision sums", so any fp32 order is legitimate; this pins
+    the library step against the literal statement (oracle/contract_plain.c: one fp32 accumulator per element, products
+    in ascending k, no blocking) at the contraction lengths of the workloads: before the rounding to storage the two
+    agree to fp32 reordering error (~sqrt(K) 2^-24 of the summed magnitudes), after it they are the same fp16 value
+    except where that difference straddles a rounding boundary (then one ulp apart), and on operands whose partial sums
+    are all exact in fp32 (small integers) they are bit-identical."""
+    from oracle.contract_plain import contract_nt
+    rng = np.random.default_rng(11)
+    for (M, N, K) in ((64, 96, 256), (33, 130, 1024), (16, 64, 4096), (8, 40, 8192)):
+        x, w = MIXED.store(rng.standard_normal((M, K))), MIXED.store(rng.standard_normal((N, K)) * 0.05)
+        lib, plain = x @ w.T, contract_nt(x, w)
+        scale = np.sqrt((x.astype(np.float64) ** 2) @ (w.astype(np.float64) ** 2).T)      # magnitude of the summed terms
+        assert np.max(np.abs(lib - plain) / scale) < 8 * np.sqrt(K) * 2.0 ** -24
+        truth = x.astype(np.float64) @ w.astype(np.float64).T
+        assert np.max(np.abs(plain - truth) / scale) < 8 * np.sqrt(K) * 2.0 ** -24         # and both sit that close to the exact sum
+        a, b = MIXED.store(lib), MIXED.store(plain)
+        differ = a != b
+        assert differ.mean() < 0.05
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(b), 2.0 ** -14))) - 10)
+        assert np.all(np.abs(a - b)[differ] <= ulp[differ] * 1.001)
+        # the layer function is that library step plus bias, ReLU and one rounding
+        bias = MIXED.store(rng.standard_normal(N))
+        y = L.linear_fwd(MIXED, x, w, bias, relu=True)
+        y_plain = MIXED.store(np.maximum(plain + bias, np.float32(0)))
+        assert (y != y_plain).mean() < 0.05 and np.linalg.norm(y - y_plain) <= 1e-4 * np.linalg.norm(y_plain)
+    xi = rng.integers(-8, 9, (40, 512)).astype(np.float32)
+    wi = rng.integers(-8, 9, (24, 512)).astype(np.float32)
+    assert np.array_equal(xi @ wi.T, contract_nt(xi, wi))                                  # every partial sum exact: order cannot matter
+    # orientation: the second operand is [N, K] (rows contract with rows)
+    e = np.zeros((3, 5), np.float32); e[1, 2] = 1
+    f = np.arange(20, dtype=np.float32).reshape(4, 5)
+    assert np.array_equal(contract_nt(e, f), e @ f.T)
