@@ -78,9 +78,9 @@ def gemm_roofline(torch, B, step, reps=20):
         "dx_ffn2": (2.0 * T * f * d, lambda: B.mp_gemm_bwd_dx(step.d_f2, dz2, w["l0.w2"], df, relu_src=a["f"], ld_aux=f)),
     }
     if step.grouped_dw:
-        grp = B.gemm_group([(step.d_f2, dz2, a["f"], g["l0.w2"]), (step.d_f1, df, a["y1"], g["l0.w1"]),
-                            (step.d_qkv, dqkv, x, g["l0.wqkv"]), (step.d_o, dz1, a["ctx"], g["l0.wo"])])
-        calls["dw_grouped(qkv,o,ffn1,ffn2)"] = (2.0 * T * (4 * d * d + 2 * f * d), lambda: B.mp_gemm_bwd_dw_grouped(grp, st))
+        grp = B.gemm_group([(step.d_f2, dz2, a["f"], g["l0.w2"]), (step.d_f1, df, a["y1"], g["l0.w1"], g["l0.b1"]),
+                            (step.d_qkv, dqkv, x, g["l0.wqkv"], g["l0.bqkv"]), (step.d_o, dz1, a["ctx"], g["l0.wo"])])
+        calls["dw_grouped(qkv,o,ffn1,ffn2 + bias gradients of ffn1, qkv)"] = (2.0 * T * (4 * d * d + 2 * f * d), lambda: B.mp_gemm_bwd_dw_grouped(grp, st))
     else:
         calls.update({
             "dw_qkv": (2.0 * T * 3 * d * d, lambda: B.mp_gemm_bwd_dw(step.d_qkv, dqkv, x, g["l0.wqkv"], None, st, ws)),
@@ -263,7 +263,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
     ap.add_argument("--one-stream", action="store_true",
-                    help="keep the weight-gradient launch and the bias-gradient column sums on the main stream")
+                    help="keep the grouped weight-gradient launch of each layer on the main stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-iterations", type=int, default=2, help="complete oracle iterations of the full workload")
     ap.add_argument("--insitu-steps", type=int, default=3, help="eager steps whose contractions are timed one by one")
@@ -362,7 +362,7 @@ def main():
                                "dynamic loss scale 2^15 / growth 100",
                    "launch": "HIP graph replay" if not args.no_graph else "eager ctypes launches",
                    "overflow_check": "in gradient-producing epilogues (MP_UPDATE_PRECHECKED)", "update_list": "one flat descriptor",
-                   "streams": "one stream" if args.one_stream else "weight-gradient launch and bias-gradient column sums of each layer on a second stream"},
+                   "streams": "one stream" if args.one_stream else "grouped weight-gradient launch of each layer (with two bias gradients in it) on a second stream"},
         "step_gemm_tflops": wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12,
         "step_mfma_util_pct": 100.0 * wl.gemm_flops_per_step() / (ms_per_step * 1e-3) * 1e-12 / PEAK_FP16_TFLOPS,
         "final_loss": loss, "loss_scale": st.scale, "opt_steps": st.opt_step, "skipped": st.skipped_steps,

@@ -188,8 +188,11 @@ int mp_gemm_bwd_dw(const mp_gemm_desc* desc /* host */, const mp_half* dY, const
  * Each of a layer's dW = dY^T X alone has too few output tiles to occupy the chip without splitting its
  * contraction; together they do.  items: host array of `count` (1..8) problems, each a descriptor as for
  * mp_gemm_bwd_dw (same meaning of M, N, K, ldx, ldw, ldy, trans_w, alpha; no batches) with its device pointers.
- * The overflow flag of `st` (may be NULL) is set if any stored gradient is non-finite.  No bias gradients here
- * (mp_colsum).  MP_E_UNSUPPORTED, with nothing launched, if an item is batched, fails the 16-byte / multiple-of-8
+ * The overflow flag of `st` (may be NULL) is set if any stored gradient is non-finite.  An item's db (device, N
+ * elements, may be NULL) receives the bias gradient RNE16(fp32 column sums of dY[M, N]) from the same launch: the
+ * sums are cut into 128-column strips that are handed to workgroups like tiles, each strip summed in a fixed
+ * order (same results contract as mp_colsum, not the same summation order).
+ * MP_E_UNSUPPORTED, with nothing launched, if an item is batched, fails the 16-byte / multiple-of-8
  * alignment rules of the fast path, or has a weight shape that is not a multiple of 128 in both dimensions or a
  * row count (M) that is not a multiple of 64: use mp_gemm_bwd_dw for those. */
 typedef struct mp_gemm_group_item {
@@ -197,6 +200,7 @@ typedef struct mp_gemm_group_item {
     const mp_half* dY;
     const mp_half* X;
     mp_half*       dW;
+    mp_half*       db;   /* may be NULL */
 } mp_gemm_group_item;
 int mp_gemm_bwd_dw_grouped(const mp_gemm_group_item* items, int count, mp_scale_state* st, mp_stream stream);
 

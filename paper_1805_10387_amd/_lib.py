@@ -33,7 +33,7 @@ class GemmDesc(C.Structure):
 
 
 class GemmGroupItem(C.Structure):
-    _fields_ = [("desc", GemmDesc), ("dY", C.c_void_p), ("X", C.c_void_p), ("dW", C.c_void_p)]
+    _fields_ = [("desc", GemmDesc), ("dY", C.c_void_p), ("X", C.c_void_p), ("dW", C.c_void_p), ("db", C.c_void_p)]
 
 
 class LstmLayerDesc(C.Structure):

@@ -109,11 +109,13 @@ def mp_gemm_bwd_dw(desc: GemmDesc, dY, X, dW, db=None, st=None, ws=None):
 
 
 def gemm_group(items):
-    """Host array for mp_gemm_bwd_dw_grouped from (desc, dY, X, dW) tuples; keeps the tensors alive."""
+    """Host array for mp_gemm_bwd_dw_grouped from (desc, dY, X, dW[, db]) tuples; keeps the tensors alive."""
     arr = (L.GemmGroupItem * len(items))()
-    for k, (desc, dY, X, dW) in enumerate(items):
+    for k, it in enumerate(items):
+        desc, dY, X, dW = it[:4]
         C.memmove(C.byref(arr[k].desc), C.byref(desc), C.sizeof(GemmDesc))
         arr[k].dY, arr[k].X, arr[k].dW = _p(dY), _p(X), _p(dW)
+        arr[k].db = _p(it[4]) if len(it) > 4 else None
     arr._keep = [t for it in items for t in it[1:]]
     return arr
 

@@ -444,6 +444,19 @@ extern "C" int mp_gemm_bwd_dw_grouped(const mp_gemm_group_item* items, int count
     }
     MP_REQUIRE(total < (1 << 24), "mp_gemm_bwd_dw_grouped: too many tiles");
     for (int i = count; i <= GROUP_MAX; ++i) ga.tile_start[i] = (int)total;
+    // bias gradients: strips of BIAS_COLS columns of dY[M, N], numbered after the product tiles (same item order)
+    int strips = 0;
+    for (int i = 0; i < count; ++i) {
+        const mp_gemm_group_item& it = items[order[i]];
+        if (!it.db) continue;
+        BiasItem& b = ga.b[ga.nbias];
+        b.dY = reinterpret_cast<const unsigned short*>(it.dY);
+        b.db = reinterpret_cast<unsigned short*>(it.db);
+        b.ld = it.desc.ldy; b.rows = it.desc.M;
+        ga.strip_start[ga.nbias++] = strips;
+        strips += it.desc.N / BIAS_COLS;      // N is a multiple of 128 here (checked above for either orientation)
+    }
+    for (int i = ga.nbias; i <= GROUP_MAX; ++i) ga.strip_start[i] = strips;
     bool k32 = true;
     for (int i = 0; i < count; ++i) k32 = k32 && ga.p[i].K % DK == 0;
     if (dtl_mode() != 0 && k32)

@@ -276,7 +276,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_dtl_grouped_kernel(GroupArg
     bool      bad_any = false;
     int*      flag    = ga.p[0].found_inf;
     const int total   = ga.tile_start[ga.count];
-    for (int vb0 = blockIdx.x; vb0 < total; vb0 += gridDim.x) {
+    const int items   = total + ga.strip_start[ga.nbias];
+    for (int vb0 = blockIdx.x; vb0 < items; vb0 += gridDim.x) {
+        if (vb0 >= total) {  // a bias-gradient strip (no ring in flight between tiles here)
+            bool bad = false;
+            group_bias_item(ga, vb0 - total, smem, bad);
+            bad_any |= bad;
+            continue;
+        }
         const int xq = total >> 3, xrem = total & 7, xx = vb0 & 7;
         const int vb = xx * xq + min(xx, xrem) + (vb0 >> 3);
         GemmArgs g     = ga.p[0];
@@ -307,7 +314,7 @@ int launch_dtl_grouped(const GroupArgs& ga, int resident, hipStream_t hs) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     if (attr_err != hipSuccess) return hip_fail(attr_err, "gemm: hipFuncSetAttribute(LDS size)");
-    const int total = ga.tile_start[ga.count];
+    const int total = ga.tile_start[ga.count] + ga.strip_start[ga.nbias];
     hipLaunchKernelGGL((gemm_dtl_grouped_kernel<BM, BN>), dim3(total < resident ? total : resident), dim3(GEMM_THREADS), lds, hs, ga);
     MP_LAUNCH_CHECK("grouped gemm launch (direct-to-LDS)");
     return MP_OK;

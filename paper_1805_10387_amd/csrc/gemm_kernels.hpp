@@ -609,11 +609,79 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs g) {
 // alone has too few tiles for the chip).  Tiles of all problems are numbered one after the other, largest problem
 // first; no batches, no k-splits.
 constexpr int GROUP_MAX = 8;
+// A bias gradient riding in a grouped launch: column sums of dY[rows, cols], cut into strips of BIAS_COLS columns
+// that are numbered after the product tiles (a strip is one work item for a workgroup, like a tile).
+constexpr int BIAS_COLS = 128;
+struct BiasItem {
+    const unsigned short* dY;  // fp16 bits
+    unsigned short*       db;
+    int                   ld, rows;
+};
 struct GroupArgs {
     GemmArgs p[GROUP_MAX];
     int      tile_start[GROUP_MAX + 1];
     int      count;
+    BiasItem b[GROUP_MAX];
+    int      strip_start[GROUP_MAX + 1];  // strip_start[nbias] = number of strips
+    int      nbias;
 };
+
+// db[strip] = RNE16(fp32 column sums of a 128-column strip of dY), by one workgroup of 256 threads: 16 lanes x 8
+// columns (16-byte loads) by 16 row groups, 8 loads in flight per thread, rows summed in a fixed order (per thread
+// ascending, then the 16 row groups ascending), so the result does not depend on scheduling.  16 x 128 floats of LDS.
+__device__ inline void colsum_strip(const BiasItem it, int strip, char* smem, bool& bad) {
+    constexpr int U = 8;
+    const int     tid = threadIdx.x, cx = tid & 15, ry = tid >> 4;
+    const unsigned short* src = it.dY + (size_t)strip * BIAS_COLS + cx * 8;
+    float         acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int r0 = ry; r0 < it.rows; r0 += 16 * U) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = r0 + 16 * u;
+            v[u]        = (r < it.rows) ? *reinterpret_cast<const uint4*>(src + (size_t)r * it.ld) : uint4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] += (float)__builtin_bit_cast(_Float16, (unsigned short)(w[e] & 0xffffu));
+                acc[2 * e + 1] += (float)__builtin_bit_cast(_Float16, (unsigned short)(w[e] >> 16));
+            }
+        }
+    }
+    float* red = reinterpret_cast<float*>(smem);
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[ry * BIAS_COLS + cx * 8 + e] = acc[e];
+    __syncthreads();
+    if (tid < BIAS_COLS) {
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += red[j * BIAS_COLS + tid];
+        const unsigned short h = __builtin_bit_cast(unsigned short, (_Float16)s);  // round to nearest even
+        it.db[(size_t)strip * BIAS_COLS + tid] = h;
+        bad |= (h & 0x7fffu) >= 0x7c00u;
+    }
+    __syncthreads();
+}
+
+// the strips of a grouped launch, work items total .. total + strips - 1
+__device__ inline void group_bias_item(const GroupArgs& ga, int s, char* smem, bool& bad) {
+    BiasItem it    = ga.b[0];
+    int      first = 0;
+#pragma unroll
+    for (int q = 1; q < GROUP_MAX; ++q) {
+        if (q < ga.nbias && s >= ga.strip_start[q]) {
+            it    = ga.b[q];
+            first = ga.strip_start[q];
+        }
+    }
+    colsum_strip(it, s - first, smem, bad);
+}
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_grouped_kernel(GroupArgs ga) {
@@ -621,7 +689,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_grouped_kernel(GroupArgs ga
     bool      bad_any = false;
     int*      flag    = ga.p[0].found_inf;  // one flag for the whole group
     const int total   = ga.tile_start[ga.count];
-    for (int vb0 = blockIdx.x; vb0 < total; vb0 += gridDim.x) {
+    const int items   = total + ga.strip_start[ga.nbias];
+    for (int vb0 = blockIdx.x; vb0 < items; vb0 += gridDim.x) {
+        if (vb0 >= total) {  // a bias-gradient strip
+            bool bad = false;
+            group_bias_item(ga, vb0 - total, smem, bad);
+            bad_any |= bad;
+            continue;
+        }
         // consecutive workgroup ids go round-robin over the 8 XCDs: give each XCD, and its L2, a contiguous run of
         // tiles (neighbouring tiles share operand panels)
         const int xq = total >> 3, xrem = total & 7, xx = vb0 & 7;
@@ -702,7 +777,7 @@ int launch_grouped(const GroupArgs& ga, int resident, hipStream_t hs) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     if (attr_err != hipSuccess) return hip_fail(attr_err, "gemm: hipFuncSetAttribute(LDS size)");
-    const int total = ga.tile_start[ga.count];
+    const int total = ga.tile_start[ga.count] + ga.strip_start[ga.nbias];
     hipLaunchKernelGGL((gemm_grouped_kernel<BM, BN, 2, 2, false, false>), dim3(total < resident ? total : resident),
                        dim3(GEMM_THREADS), lds, hs, ga);
     MP_LAUNCH_CHECK("grouped gemm launch");

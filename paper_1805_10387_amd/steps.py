@@ -268,9 +268,7 @@ class TransformerStep(_StepBase):
                 fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f2, dz2, a["f"], g[p + "w2"], None, st, wsx))
             B.mp_gemm_bwd_dx(self.d_f2, dz2, w[p + "w2"], df, relu_src=a["f"], ld_aux=f)
             self._t("df", l, df)
-            if self.grouped_dw:
-                fork(lambda wsx: B.mp_colsum(T, f, df, f, g[p + "b1"], st, wsx))
-            else:
+            if not self.grouped_dw:
                 fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_f1, df, a["y1"], g[p + "w1"], g[p + "b1"], st, wsx))
             B.mp_gemm_bwd_dx(self.d_f1, df, w[p + "w1"], self.dy1, add=dz2, ld_aux=d)
             self._t("dy1", l, self.dy1)
@@ -293,18 +291,20 @@ class TransformerStep(_StepBase):
                 B.mp_gemm_bwd_dx(self.d_s, self.dp, a["qkv"][:, d:], dqkv)
                 B.mp_gemm_bwd_dw(self.d_s, self.dp, a["qkv"], dqkv[:, d:], None, None, ws)
             self._t("dqkv", l, dqkv)
-            if self.grouped_dw:
-                fork(lambda wsx: B.mp_colsum(T, 3 * d, dqkv, 3 * d, g[p + "bqkv"], st, wsx))
-            else:
+            if not self.grouped_dw:
                 fork(lambda wsx: B.mp_gemm_bwd_dw(self.d_qkv, dqkv, x, g[p + "wqkv"], g[p + "bqkv"], st, wsx))
             B.mp_gemm_bwd_dx(self.d_qkv, dqkv, w[p + "wqkv"], dx, add=dz1, ld_aux=d)
             self._t("dx", l, dx)
             if self.grouped_dw:
-                # all four operand pairs of this layer are still in place (the temporaries alternate by layer)
+                # all four operand pairs of this layer are still in place (the temporaries alternate by layer); the
+                # two bias gradients that no LayerNorm backward produced ride in the same launch, on CUs that the
+                # product tiles (fewer than the chip has CUs) leave idle
                 key = (l, i % 2)
                 if key not in self._groups:
-                    self._groups[key] = B.gemm_group([(self.d_f2, dz2, a["f"], g[p + "w2"]), (self.d_f1, df, a["y1"], g[p + "w1"]),
-                                                      (self.d_qkv, dqkv, x, g[p + "wqkv"]), (self.d_o, dz1, a["ctx"], g[p + "wo"])])
+                    self._groups[key] = B.gemm_group([(self.d_f2, dz2, a["f"], g[p + "w2"]),
+                                                      (self.d_f1, df, a["y1"], g[p + "w1"], g[p + "b1"]),
+                                                      (self.d_qkv, dqkv, x, g[p + "wqkv"], g[p + "bqkv"]),
+                                                      (self.d_o, dz1, a["ctx"], g[p + "wo"])])
                 fork(lambda wsx: B.mp_gemm_bwd_dw_grouped(self._groups[key], st))
             if side is not None:
                 done[i] = torch.cuda.Event()

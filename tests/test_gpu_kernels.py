@@ -334,15 +334,18 @@ def test_gemm_split_k_weight_gradient():
 def test_gemm_grouped_weight_gradients(shapes):
     """Several dW = dY^T X in one launch: each equals the oracle and, bit for bit, the single-problem entry point."""
     r = RNG(len(shapes) * 7 + shapes[0][1])
-    items, refs, singles = [], [], []
+    items, refs, singles, db_refs = [], [], [], []
     st = make_state()
     all256 = all(n % 256 == 0 and k % 256 == 0 for (_, n, k) in shapes)
-    for (M, N, K) in shapes:
+    for j, (M, N, K) in enumerate(shapes):
         x, dy = S16(r.standard_normal((M, K))), S16(r.standard_normal((M, N)) * 0.1)
         d = mp.gemm_desc(M, N, K)
         dw, dw1 = empty16(N, K), empty16(N, K)
-        items.append((d, h16(dy), h16(x), dw))
-        refs.append(L.linear_bwd(MIXED, dy, x, np.zeros((N, K), np.float32))[1])
+        # every item but the second also asks for its bias gradient from the same launch
+        items.append((d, h16(dy), h16(x), dw) + ((empty16(N),) if j != 1 else ()))
+        _, dw_ref, db_ref = L.linear_bwd(MIXED, dy, x, np.zeros((N, K), np.float32))
+        refs.append(dw_ref)
+        db_refs.append(db_ref)
         mp.mp_gemm_tuning_override(0 if all256 else 3, 1)         # the tile the grouped launch takes, no k-split
         mp.mp_gemm_bwd_dw(d, items[-1][1], items[-1][2], dw1, None, None, ws_bytes(mp.mp_gemm_bwd_dw_workspace_bytes(d, False)))
         mp.mp_gemm_tuning_override(-1, 0)
@@ -351,13 +354,16 @@ def test_gemm_grouped_weight_gradients(shapes):
         mp.mp_gemm_tuning_dtl(mode)
         try:
             for it in items:
-                it[3].zero_()
+                for out in it[3:]:
+                    out.fill_(float("nan"))
             mp.mp_gemm_bwd_dw_grouped(mp.gemm_group(items), st)
         finally:
             mp.mp_gemm_tuning_dtl(1)
         for k, (it, ref, one) in enumerate(zip(items, refs, singles)):
             assert_close16(it[3], ref, 1e-3, max_ulp=1, what=f"grouped dw {k} (mode {mode})")
             assert torch.equal(it[3], one), f"grouped dw {k} differs from the single-problem result (mode {mode})"
+            if len(it) > 4:
+                assert_close16(it[4], db_refs[k], 1e-3, max_ulp=1, what=f"grouped db {k} (mode {mode})")
     assert mp.scale_state_read(st).found_inf == 0
 
 
@@ -372,6 +378,12 @@ def test_gemm_grouped_flags_overflow_and_rejects_ragged_shapes():
     mp.mp_gemm_bwd_dw_grouped(mp.gemm_group([(d, ok_dy, ok_x, dw0), (d, big, x, dw1)]), st)
     assert mp.scale_state_read(st).found_inf == 1          # 128 * 300 * 300 overflows fp16
     assert torch.all(dw0 == 128.0) and torch.all(torch.isinf(dw1))
+    # a bias gradient that overflows while the product stays finite: 128 rows of 600 sum to 76800 > 65504
+    st2 = make_state()
+    dy600 = torch.full((M, N), 600.0, dtype=torch.float16, device="cuda")
+    zeros, db = torch.zeros(M, K, dtype=torch.float16, device="cuda"), empty16(N)
+    mp.mp_gemm_bwd_dw_grouped(mp.gemm_group([(d, dy600, zeros, dw0, db)]), st2)
+    assert mp.scale_state_read(st2).found_inf == 1 and torch.all(dw0 == 0.0) and torch.all(torch.isinf(db))
     bad = mp.gemm_desc(128, 136, 128)
     with pytest.raises(mp.MPError) as e:
         mp.mp_gemm_bwd_dw_grouped(mp.gemm_group([(bad, empty16(128, 136), ok_x, empty16(136, 128))]), st)
