@@ -1,7 +1,8 @@
 // Contraction kernel whose operand tiles go from global memory straight into LDS (no staging registers, no LDS store
-// instructions) through a ring of 32-deep k-tiles (four stages for the 256 x 256 tile, more for smaller tiles), for interior problems (every tile inside the matrices, K a
-// multiple of 32).  Same arithmetic and epilogue as gemm_kernels.hpp (paper Section 3.1: fp16 operands, fp32 sums,
-// one rounding); what differs is how the operands reach the matrix cores.
+// instructions) through a ring of 32-deep k-tiles (as many stages as fit 160 KB of LDS: five for the 256 x 256 tile,
+// up to eight for smaller tiles), for interior problems (every tile inside the matrices, K a multiple of 32).  Same
+// arithmetic and epilogue as gemm_kernels.hpp (paper Section 3.1: fp16 operands, fp32 sums, one rounding); what
+// differs is how the operands reach the matrix cores.
 //
 //   * `global_load_lds` (16 bytes per lane): a wave instruction deposits its 64 lanes' pieces as 1 KB of CONSECUTIVE
 //     LDS bytes in lane order, whatever each lane's global address is.  The LDS layout is therefore chosen by choosing
@@ -14,9 +15,10 @@
 //         addressed by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4, so four lanes that address the same k and four
 //         consecutive 4-row groups hand every lane of the 16 its own row at 4 consecutive k.  Two such reads make the
 //         8-k fragment of `v_mfma_f32_32x32x16_f16`; no byte permutes, no register transposes.
-//   * ring of four stages: the loads of k-tile q + 4 are issued right behind the barrier inside k-tile q that retires
-//     stage q % 4, so a tile has three k-tiles of matrix-core work (about 3 x 1024 cycles) to arrive, and the ring runs
-//     on across output tiles: the next tile's first k-tiles are requested during the current tile's last ones.
+//   * ring of DNS stages: the loads of k-tile q + DNS are issued right behind the barrier inside k-tile q that retires
+//     stage q % DNS, so a k-tile has DNS - 1 k-tiles of matrix-core work (about 1024 cycles each for the 256 x 256 tile)
+//     to arrive, and the ring runs on across output tiles: the next tile's first k-tiles are requested during the
+//     current tile's last ones.
 //   * one workgroup barrier per k-tile, placed between its two 16-deep slices: behind it come the fragment reads of
 //     the next k-tile's first slice, covered by the matrix-core work of this k-tile's second slice.
 #pragma once
@@ -144,7 +146,7 @@ __device__ __forceinline__ void dtl_tiles(const GemmArgs& g, const int vb0, cons
     const long long step_a = A_KC ? DK : (long long)DK * g.lda;
     const long long step_b = B_KC ? DK : (long long)DK * g.ldb;
 
-    // ---- the load stream: k-tile after k-tile, output tile after output tile, into stage (count % 4)
+    // ---- the load stream: k-tile after k-tile, output tile after output tile, into stage (count % DNS)
     int             l_vb = vb0, l_kt = 0, l_stage = 0;
     const uint16_t *l_pa = nullptr, *l_pb = nullptr;
     auto            l_origin = [&] {
@@ -191,7 +193,7 @@ __device__ __forceinline__ void dtl_tiles(const GemmArgs& g, const int vb0, cons
         else bf[buf][f - TM] = ob.template frag<kk, f - TM>(stage + OpA::BYTES);
     };
 
-    // prologue: four k-tiles on their way, the first landed, its first fragments in registers
+    // prologue: DNS k-tiles on their way, the first landed, its first fragments in registers
     static_for<DNS>([&](auto) { issue_next(); });
     static_assert((DNS - 1) * LPW <= 63, "loads in flight must fit the counter");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DNS - 1) * LPW) : "memory");
@@ -233,7 +235,7 @@ __device__ __forceinline__ void dtl_tiles(const GemmArgs& g, const int vb0, cons
                 if constexpr (m < NR) read_frag_one(cur, std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, mc);
                 __builtin_amdgcn_sched_barrier(0);
             });
-            // the next k-tile has landed (two later ones may still be in flight), and every wave is done with this stage:
+            // the next k-tile has landed (DNS - 2 later ones may still be in flight), and every wave is done with this stage:
             // its last fragments are in registers
             asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((DNS - 2) * LPW) : "memory");
             __builtin_amdgcn_s_barrier();

@@ -143,8 +143,14 @@ struct OCLoader {  // operand stored [k][row]; `tile` points at element (k0, row
     unsigned lane_off;
     int      lds_row0;  // byte offset of (row rg*8, k kg*KB) before the slot swizzle: row*128 + within-slot bytes
     int      lds_slot;  // (slot of k = kg*KB) ^ (rg & 7); slot(i) = lds_slot ^ i   [swz(rg*8 + i) = (i ^ rg) & 7]
+    // Which block a lane owns.  R = 128 stores 8 bytes per lane, and the LDS takes such a store 16 lanes (128 bytes, one
+    // pass over its banks) at a time: with rg = tid % 16 the 16 lanes of a pass would share one k group, i.e. the same
+    // 8-byte half of their 16-byte slots, and only 8 slots exist per pass: a two-way conflict on every store.  So a
+    // pass holds 8 row groups x 2 adjacent k groups (the two halves of a slot) instead.
+    static __device__ __forceinline__ int row_group(int t) { return R == 128 ? ((t & 7) | ((t >> 1) & 8)) : t % G; }
+    static __device__ __forceinline__ int k_group(int t) { return R == 128 ? (((t >> 3) & 1) | ((t >> 5) << 1)) : t / G; }
     __device__ __forceinline__ void init(int ld) {
-        const int rg = threadIdx.x % G, kg = threadIdx.x / G;
+        const int rg = row_group(threadIdx.x), kg = k_group(threadIdx.x);
         const int k  = kg * KB;
         lane_off = (unsigned)k * (unsigned)ld + rg * 8;
         lds_row0 = rg * 8 * 128 + (k & 7) * 2;
@@ -154,7 +160,7 @@ struct OCLoader {  // operand stored [k][row]; `tile` points at element (k0, row
     __device__ __forceinline__ void load_one(const uint16_t* tile, int ld, int rows_left, int k_left) {
         const uint16_t* p = tile + (long long)J * ld + lane_off;
         if (GUARD) {
-            const int rg = threadIdx.x % G, kg = threadIdx.x / G;
+            const int rg = row_group(threadIdx.x), kg = k_group(threadIdx.x);
             v[J] = (kg * KB + J < k_left) ? load8_guard(p, rows_left - rg * 8) : u32x4{0u, 0u, 0u, 0u};
         } else {
             v[J] = *reinterpret_cast<const u32x4*>(p);

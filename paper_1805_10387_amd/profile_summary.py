@@ -4,6 +4,7 @@
   python -m paper_1805_10387_amd.profile_summary traffic <fetch_counter_collection.csv> <write_counter_collection.csv> <out.txt>
                                                          --command-fetch C1 --command-write C2
   python -m paper_1805_10387_amd.profile_summary counters <counter_collection.csv> <out.txt> --title T --command C
+  python -m paper_1805_10387_amd.profile_summary mfma     <counter_collection.csv> <out.txt> --title T --command C [--note N ...]
 
 `traffic` also writes the two machine-readable lines bench.py reads for its `roofline.traffic` fields:
   gemm_traffic_bytes_per_launch = <bytes>      update_traffic_bytes_per_launch = <bytes>
@@ -115,6 +116,34 @@ def counters(a):
     open(a.out, "w").write("\n".join(out) + "\n")
 
 
+def mfma(a):
+    """Derived per-kernel figures from one --pmc run holding SQ_VALU_MFMA_BUSY_CYCLES, GRBM_GUI_ACTIVE, SQ_WAIT_ANY,
+    SQ_WAVE_CYCLES, SQ_ACTIVE_INST_LDS, SQ_LDS_BANK_CONFLICT and SQ_INSTS_VALU_MFMA_MOPS_F16."""
+    agg = collections.defaultdict(lambda: collections.defaultdict(float))
+    disp = collections.defaultdict(set)
+    for r in csv.DictReader(open(a.csv)):
+        k = _short(r["Kernel_Name"])
+        agg[k][r["Counter_Name"]] += float(r["Counter_Value"])
+        disp[k].add(r["Dispatch_Id"])
+    out = [a.title, "", "command (from /tmp, TMPDIR=/tmp, repo at /root/repo; eager launches, short run: counter collection serialises dispatches):",
+           "  " + a.command, "",
+           "GRBM_GUI_ACTIVE is summed over the 8 XCDs, SQ_VALU_MFMA_BUSY_CYCLES over the 1024 SIMDs:",
+           "  MFMA busy % = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / 8 * 1024).",
+           "wait any % = SQ_WAIT_ANY / SQ_WAVE_CYCLES, LDS active % = SQ_ACTIVE_INST_LDS / SQ_WAVE_CYCLES, bank conflicts = SQ_LDS_BANK_CONFLICT per",
+           "launch.  SQ_INSTS_VALU_MFMA_MOPS_F16 x 512 is the flop count the hardware saw per launch: it equals 2 M N K of the launch.", ""]
+    out.append(f"{'kernel':<62}{'launches':>9}{'GUI cyc/8':>12}{'MFMA busy %':>12}{'wait any %':>11}{'LDS act %':>10}{'bank conf':>11}{'flop':>12}")
+    keep = [k for k in agg if agg[k].get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) > 0.0]
+    for k in sorted(keep, key=lambda x: -agg[x]["SQ_VALU_MFMA_BUSY_CYCLES"]):
+        c, n = agg[k], len(disp[k])
+        gui = c["GRBM_GUI_ACTIVE"] / 8.0
+        wave = max(c["SQ_WAVE_CYCLES"], 1.0)
+        out.append(f"{k[:60]:<62}{n:>9}{gui / n:>12.0f}{100.0 * c['SQ_VALU_MFMA_BUSY_CYCLES'] / (gui * 1024.0):>12.1f}"
+                   f"{100.0 * c['SQ_WAIT_ANY'] / wave:>11.1f}{100.0 * c['SQ_ACTIVE_INST_LDS'] / wave:>10.1f}"
+                   f"{c['SQ_LDS_BANK_CONFLICT'] / n:>11.0f}{512.0 * c['SQ_INSTS_VALU_MFMA_MOPS_F16'] / n:>12.4g}")
+    out += [""] + list(a.note or [])
+    open(a.out, "w").write("\n".join(out) + "\n")
+
+
 def main():
     ap = argparse.ArgumentParser(prog="python -m paper_1805_10387_amd.profile_summary")
     sub = ap.add_subparsers(dest="what", required=True)
@@ -130,6 +159,10 @@ def main():
     p.add_argument("csv"); p.add_argument("out"); p.add_argument("--title", required=True); p.add_argument("--command", required=True)
     p.add_argument("--note", action="append")
     p.set_defaults(fn=counters)
+    p = sub.add_parser("mfma")
+    p.add_argument("csv"); p.add_argument("out"); p.add_argument("--title", required=True); p.add_argument("--command", required=True)
+    p.add_argument("--note", action="append")
+    p.set_defaults(fn=mfma)
     a = ap.parse_args()
     a.fn(a)
 
