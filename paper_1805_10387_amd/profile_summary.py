@@ -19,6 +19,8 @@ import re
 
 
 def _short(name: str) -> str:
+    if "mfma_rate_kernel" in name:          # reported with its mangled name
+        return "mfma_rate_kernel (probe)"
     name = name.replace("void ", "").replace("mp::", "")
     return re.sub(r"\(.*$", "", name)[:78]
 
