@@ -367,6 +367,29 @@ def test_gemm_grouped_weight_gradients(shapes):
     assert mp.scale_state_read(st).found_inf == 0
 
 
+def test_gemm_grouped_transposed_weight_layout_with_bias_gradient():
+    """A grouped item whose weight is stored [K, N] (trans_w): dW[K, N] = X^T dY, and db = column sums of dY, next to an
+    ordinary item; both kernel families."""
+    r = RNG(77)
+    M, N, K = 192, 256, 384
+    x, dy = S16(r.standard_normal((M, K))), S16(r.standard_normal((M, N)) * 0.1)
+    _, dw_ref, db_ref = L.linear_bwd(MIXED, dy, x, np.zeros((N, K), np.float32))
+    dt = mp.gemm_desc(M, N, K, ldw=N, trans_w=1)
+    dn = mp.gemm_desc(M, N, K)
+    for mode in (1, 0):
+        dwt, dbt, dwn = empty16(K, N), empty16(N), empty16(N, K)
+        for t in (dwt, dbt, dwn):
+            t.fill_(float("nan"))
+        mp.mp_gemm_tuning_dtl(mode)
+        try:
+            mp.mp_gemm_bwd_dw_grouped(mp.gemm_group([(dt, h16(dy), h16(x), dwt, dbt), (dn, h16(dy), h16(x), dwn)]), None)
+        finally:
+            mp.mp_gemm_tuning_dtl(1)
+        assert_close16(dwt, dw_ref.T, 1e-3, max_ulp=1, what=f"grouped dw, [K, N] layout (mode {mode})")
+        assert_close16(dwn, dw_ref, 1e-3, max_ulp=1, what=f"grouped dw (mode {mode})")
+        assert_close16(dbt, db_ref, 1e-3, max_ulp=1, what=f"grouped db (mode {mode})")
+
+
 def test_gemm_grouped_flags_overflow_and_rejects_ragged_shapes():
     M, N, K = 128, 128, 128
     big = torch.full((M, N), 300.0, dtype=torch.float16, device="cuda")
