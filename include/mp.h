@@ -8,7 +8,7 @@
  *
  *   forward  : mp_gemm_fwd[_ws] (+ mp_layernorm_fwd, mp_attention_fwd | mp_softmax_fwd,
  *              mp_lstm_cell_fwd | mp_lstm_layer_fwd)
- *   loss     : mp_mse_scaled | mp_softmax_xent_scaled      (seed gradient x loss scale)
+ *   loss     : mp_mse_scaled | mp_softmax_xent_scaled[_db] (seed gradient x loss scale)
  *   backward : mp_gemm_bwd_dx[_ws], mp_gemm_bwd_dw | mp_gemm_bwd_dw_grouped (+ mp_layernorm_bwd,
  *              mp_attention_bwd | mp_softmax_bwd, mp_lstm_cell_bwd | mp_lstm_layer_bwd, mp_colsum)
  *   update   : mp_unscale_check_update   (inspect fp16 gradients, unscale, SGD/Adam on
@@ -259,6 +259,18 @@ int mp_mse_scaled(int rows, int cols, const mp_half* y, const mp_half* target, i
 int mp_softmax_xent_scaled(int rows, int vocab, const mp_half* logits, int ld, const int32_t* targets,
                            const mp_scale_state* st, float* loss, mp_half* dlogits, void* ws,
                            size_t ws_bytes, mp_stream stream);
+
+/* mp_softmax_xent_scaled that also returns the bias gradient of the projection behind the logits (Section 3.2: the
+ * gradients are fp16 tensors): db[vocab] = RNE16( fp32 column sums over the rows of the dlogits values as stored ).
+ * For vocabularies of more than 16384 classes (multiples of 8, 16-byte aligned rows) the sums are taken in the pass
+ * that writes dlogits, so the gradient matrix is not read again; other shapes run the plain call followed by mp_colsum.
+ * st is read for S as above; its overflow flag is set if a stored db value is non-finite (dlogits itself is bounded
+ * by S / rows and is covered by whoever consumes it).  Workspace: mp_softmax_xent_db_workspace_bytes(rows, vocab),
+ * 16-byte aligned.  Same results contract as the two separate calls (fp32 summation order differs). */
+size_t mp_softmax_xent_db_workspace_bytes(int rows, int vocab);
+int mp_softmax_xent_scaled_db(int rows, int vocab, const mp_half* logits, int ld, const int32_t* targets,
+                              mp_scale_state* st, float* loss, mp_half* dlogits, mp_half* db, void* ws,
+                              size_t ws_bytes, mp_stream stream);
 
 /* ------------------------------------------------------------------------------------------
  * Bandwidth-bound layer pieces (fp32 arithmetic between fp16 storage points, Section 3.2).

@@ -77,6 +77,8 @@ SIGNATURES = {
     "mp_loss_workspace_bytes": (_SZ, [_I, _I]),
     "mp_mse_scaled": (_I, [_I, _I, _P, _P, _I, _P, _P, _P, _P, _SZ, _P]),
     "mp_softmax_xent_scaled": (_I, [_I, _I, _P, _I, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mp_softmax_xent_db_workspace_bytes": (_SZ, [_I, _I]),
+    "mp_softmax_xent_scaled_db": (_I, [_I, _I, _P, _I, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "mp_layernorm_fwd": (_I, [_I, _I, _P, _P, _P, _P, _F, _P, _P, _P, _P]),
     "mp_layernorm_bwd_workspace_bytes": (_SZ, [_I, _I]),
     "mp_layernorm_bwd": (_I, [_I, _I, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),

@@ -164,6 +164,15 @@ def mp_softmax_xent_scaled(rows, vocab, logits, ld, targets, st, loss, dlogits, 
                                            _p(ws), ws.numel() * ws.element_size(), _stream()))
 
 
+def mp_softmax_xent_db_workspace_bytes(rows: int, vocab: int) -> int:
+    return int(L.load().mp_softmax_xent_db_workspace_bytes(rows, vocab))
+
+
+def mp_softmax_xent_scaled_db(rows, vocab, logits, ld, targets, st, loss, dlogits, db, ws):
+    _check(L.load().mp_softmax_xent_scaled_db(rows, vocab, _p(logits), ld, _p(targets), _p(st), _p(loss), _p(dlogits),
+                                              _p(db), _p(ws), ws.numel() * ws.element_size(), _stream()))
+
+
 # ------------------------------------------------------------------ bandwidth-bound pieces
 def mp_layernorm_fwd(rows, d, x, a, gamma, beta, eps, y, mean, rstd):
     _check(L.load().mp_layernorm_fwd(rows, d, _p(x), _p(a), _p(gamma), _p(beta), eps, _p(y), _p(mean), _p(rstd), _stream()))

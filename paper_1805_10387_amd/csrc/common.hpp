@@ -27,6 +27,10 @@ int  hip_fail(hipError_t e, const char* what);
         if (e__ != hipSuccess) return ::mp::hip_fail(e__, what); \
     } while (0)
 
+// db[cols] = RNE16(sum over the nparts rows of part[nparts][cols]), summed in ascending order; sets st->found_inf (st may
+// be NULL) if a stored value is non-finite.  Defined beside the column-sum kernels (glue.hip).
+int finish_colsum_launch(const float* part, int nparts, int cols, mp_half* db, mp_scale_state* st, hipStream_t hs);
+
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline hipStream_t as_stream(mp_stream s) { return reinterpret_cast<hipStream_t>(s); }
 

@@ -511,6 +511,14 @@ extern "C" size_t mp_colsum_workspace_bytes(int rows, int cols) {
     return (size_t)(rb8 > rb1 ? rb8 : rb1) * cols * sizeof(float);
 }
 
+int mp::finish_colsum_launch(const float* part, int nparts, int cols, mp_half* db, mp_scale_state* st, hipStream_t hs) {
+    FinishOuts outs{{db, nullptr, nullptr}};
+    hipLaunchKernelGGL(finish_colsum_kernel, dim3((cols + 31) / 32), dim3(GL_THREADS), 0, hs, part, nparts, (long long)cols,
+                       cols, 1, outs, st);
+    MP_LAUNCH_CHECK("column-sum finish");
+    return MP_OK;
+}
+
 // Both launches of a column sum; `part` holds mp_colsum_workspace_bytes(rows, cols) bytes of partial sums, every one of
 // which the first launch writes before the second reads it (nothing has to start at zero).
 static int colsum_launch(int rows, int cols, const mp_half* dY, int ld, mp_half* db, mp_scale_state* st, float* part,

@@ -85,12 +85,16 @@ __device__ __forceinline__ float block_reduce_lds(float v, float* red) {
 // Workgroups are persistent over rows (row = blockIdx.x, + gridDim.x, ...): the packed logits of the next row are
 // requested before the current row is reduced, so the two reductions and the exponentials of a row run under the
 // next row's memory latency.
-template <int THREADS>
+// COLSUM: every workgroup also sums the gradient values it stores (the fp16 values, as stored) per column over its
+// rows, and leaves the sums in colpart[blockIdx.x][vocab]: the bias gradient of the projection that made the logits
+// then needs no second pass over the gradient matrix, only a sum over gridDim.x partial rows.
+template <int THREADS, bool COLSUM = false>
 __global__ __launch_bounds__(THREADS) void xent_cached_kernel(int vocab, int ld, const uint16_t* logits,
                                                               const int32_t* __restrict__ targets,
                                                               const mp_scale_state* __restrict__ st, int rows,
                                                               uint16_t* dlogits,  // may alias logits
-                                                              float* __restrict__ row_loss) {
+                                                              float* __restrict__ row_loss,
+                                                              float* __restrict__ colpart = nullptr) {
     __shared__ float red[THREADS / 64];
     const int        nvec  = vocab >> 3;
     const float      coef0 = (float)((double)st->scale / (double)rows);
@@ -110,6 +114,13 @@ __global__ __launch_bounds__(THREADS) void xent_cached_kernel(int vocab, int ld,
     int   tgt = -1;
     float zt  = 0.f;
     int   row = blockIdx.x;
+    float cs[COLSUM ? XENT_VECS : 1][8];
+    if (COLSUM) {
+#pragma unroll
+        for (int i = 0; i < XENT_VECS; ++i)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) cs[i][k] = 0.f;
+    }
     if (row < rows) fetch(row, raw, tgt, zt);
     for (; row < rows; row += gridDim.x) {
         // (the next row is another row of the same matrix: it is read before anything is written to it, also when
@@ -162,12 +173,30 @@ __global__ __launch_bounds__(THREADS) void xent_cached_kernel(int vocab, int ld,
 #pragma unroll
                 for (int k = 0; k < 4; ++k) o[k] = (unsigned)f2h(coef * p[2 * k]) | ((unsigned)f2h(coef * p[2 * k + 1]) << 16);
                 *reinterpret_cast<uint4*>(dz + (long long)v * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+                if (COLSUM) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        cs[i][2 * k] += h2f((uint16_t)(o[k] & 0xFFFFu));
+                        cs[i][2 * k + 1] += h2f((uint16_t)(o[k] >> 16));
+                    }
+                }
             }
         }
 #pragma unroll
         for (int i = 0; i < XENT_VECS; ++i) raw[i] = nraw[i];
         tgt = ntgt;
         zt  = nzt;
+    }
+    if (COLSUM) {
+        float* out = colpart + (long long)blockIdx.x * vocab;
+#pragma unroll
+        for (int i = 0; i < XENT_VECS; ++i) {
+            const int v = i * THREADS + threadIdx.x;
+            if (v < nvec) {
+                *reinterpret_cast<float4*>(out + (long long)v * 8)     = make_float4(cs[i][0], cs[i][1], cs[i][2], cs[i][3]);
+                *reinterpret_cast<float4*>(out + (long long)v * 8 + 4) = make_float4(cs[i][4], cs[i][5], cs[i][6], cs[i][7]);
+            }
+        }
     }
 }
 
@@ -282,4 +311,49 @@ extern "C" int mp_softmax_xent_scaled(int rows, int vocab, const mp_half* logits
     hipLaunchKernelGGL(finish_mean_kernel, dim3(1), dim3(LOSS_THREADS), 0, hs, row_loss, rows, (double)rows, loss);
     MP_LAUNCH_CHECK("mp_softmax_xent_scaled(finish)");
     return MP_OK;
+}
+
+// ---- cross-entropy that also leaves the bias gradient of the projection behind the logits
+static size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+// the fused path: rows cached in a 1024-lane workgroup, workgroups persistent over rows
+static bool xent_db_fused(int rows, int vocab, int ld, const void* logits, const void* dlogits) {
+    return (vocab % 8 == 0) && (ld % 8 == 0) && aligned16(logits) && aligned16(dlogits) && vocab / 8 <= XENT_VECS * 1024 &&
+           vocab / 8 > XENT_VECS * 512 && rows >= 1;
+}
+
+extern "C" size_t mp_softmax_xent_db_workspace_bytes(int rows, int vocab) {
+    if (rows <= 0 || vocab <= 0) return 0;
+    const size_t fused = (size_t)xent_grid(rows, 1024) * (size_t)vocab * sizeof(float);
+    const size_t plain = mp_colsum_workspace_bytes(rows, vocab);
+    return round256(mp_loss_workspace_bytes(rows, vocab)) + (fused > plain ? fused : plain);
+}
+
+extern "C" int mp_softmax_xent_scaled_db(int rows, int vocab, const mp_half* logits, int ld, const int32_t* targets,
+                                         mp_scale_state* st, float* loss, mp_half* dlogits, mp_half* db, void* ws,
+                                         size_t ws_bytes, mp_stream stream) {
+    MP_REQUIRE(rows > 0 && vocab > 0 && ld >= vocab, "mp_softmax_xent_scaled_db: bad shape rows=%d vocab=%d ld=%d", rows,
+               vocab, ld);
+    MP_REQUIRE(logits && targets && st && loss && dlogits && db, "mp_softmax_xent_scaled_db: NULL argument");
+    if (!ws || ws_bytes < mp_softmax_xent_db_workspace_bytes(rows, vocab) || !aligned16(ws)) {
+        set_error("mp_softmax_xent_scaled_db: 16-byte aligned workspace of %zu bytes needed, %zu given",
+                  mp_softmax_xent_db_workspace_bytes(rows, vocab), ws_bytes);
+        return MP_E_WORKSPACE;
+    }
+    const size_t head = round256(mp_loss_workspace_bytes(rows, vocab));
+    float*       part = reinterpret_cast<float*>(static_cast<char*>(ws) + head);
+    hipStream_t  hs   = as_stream(stream);
+    if (!xent_db_fused(rows, vocab, ld, logits, dlogits)) {
+        // small or unaligned vocabularies: the plain loss call, then a column sum over the gradient it stored
+        const int rc = mp_softmax_xent_scaled(rows, vocab, logits, ld, targets, st, loss, dlogits, ws, head, stream);
+        if (rc != MP_OK) return rc;
+        return mp_colsum(rows, vocab, dlogits, ld, db, st, part, ws_bytes - head, stream);
+    }
+    float*    row_loss = static_cast<float*>(ws);
+    const int grid     = xent_grid(rows, 1024);
+    hipLaunchKernelGGL((xent_cached_kernel<1024, true>), dim3(grid), dim3(1024), 0, hs, vocab, ld, logits, targets, st, rows,
+                       dlogits, row_loss, part);
+    MP_LAUNCH_CHECK("mp_softmax_xent_scaled_db");
+    hipLaunchKernelGGL(finish_mean_kernel, dim3(1), dim3(LOSS_THREADS), 0, hs, row_loss, rows, (double)rows, loss);
+    MP_LAUNCH_CHECK("mp_softmax_xent_scaled_db(finish)");
+    return finish_colsum_launch(part, grid, vocab, db, st, hs);
 }

@@ -333,7 +333,7 @@ class XentStep(_StepBase):
         self.logits = torch.empty(T, V, dtype=torch.float16, device="cuda")   # overwritten by dlogits
         self.dh = torch.empty(T, d, dtype=torch.float16, device="cuda")
         self.desc = B.gemm_desc(T, V, d, epilogue=ML.MP_EPI_BIAS)
-        self._alloc_ws(max(B.mp_gemm_bwd_dw_workspace_bytes(self.desc, True), B.mp_loss_workspace_bytes(T, V)))
+        self._alloc_ws(max(B.mp_gemm_bwd_dw_workspace_bytes(self.desc, False), B.mp_softmax_xent_db_workspace_bytes(T, V)))
 
     def set_batch(self, batch):
         self.h.copy_(_h16(batch["h"]))
@@ -343,8 +343,9 @@ class XentStep(_StepBase):
         wl, w, g = self.wl, self.P.w16, self.P.g16
         T, V = wl.tokens, wl.vocab
         B.mp_gemm_fwd(self.desc, self.h, w["w"], w["b"], None, self.logits)
-        B.mp_softmax_xent_scaled(T, V, self.logits, V, self.targets, self.st, self.loss, self.logits, self.ws)
-        B.mp_gemm_bwd_dw(self.desc, self.logits, self.h, g["w"], g["b"], self.st_grad, self.ws)
+        # the bias gradient (column sums of dlogits) comes out of the pass that writes dlogits
+        B.mp_softmax_xent_scaled_db(T, V, self.logits, V, self.targets, self.st, self.loss, self.logits, g["b"], self.ws)
+        B.mp_gemm_bwd_dw(self.desc, self.logits, self.h, g["w"], None, self.st_grad, self.ws)
         B.mp_gemm_bwd_dx(self.desc, self.logits, w["w"], self.dh)
 
 

@@ -533,6 +533,53 @@ def test_softmax_xent_scaled(rows, vocab):
     assert np.array_equal(bits(zd), bits(g))
 
 
+@pytest.mark.parametrize("rows,vocab", [(600, 32768), (300, 24584), (16, 32768), (33, 3000), (7, 1001)])
+def test_softmax_xent_scaled_with_bias_gradient(rows, vocab):
+    """The loss call that also sums the stored gradient per column (the bias gradient of the projection): same loss and
+    the same gradient bits as the plain call, db equal to the oracle's column sums of that gradient; the first two shapes
+    take the fused pass (several rows per persistent workgroup), the others the plain call followed by mp_colsum."""
+    r = RNG(3 * rows + vocab)
+    z = S16(r.standard_normal((rows, vocab)) * 3)
+    t = r.integers(0, vocab, rows).astype(np.int32)
+    t[1], t[2] = -1, vocab
+    S = 2.0 ** 15
+    loss_ref, g_ref = L.softmax_xent_scaled(MIXED, z, t, S)
+    db_ref = L.linear_bwd(MIXED, g_ref, np.zeros((rows, 8), np.float32), np.zeros((vocab, 8), np.float32))[2]
+    st = make_state(scale=S)
+    loss, loss2, g, g2, db = empty32(1), empty32(1), empty16(rows, vocab), empty16(rows, vocab), empty16(vocab)
+    db.fill_(float("nan"))
+    zd = h16(z)
+    mp.mp_softmax_xent_scaled(rows, vocab, zd, vocab, i32(t), st, loss, g, ws_bytes(mp.mp_loss_workspace_bytes(rows, vocab)))
+    ws = ws_bytes(mp.mp_softmax_xent_db_workspace_bytes(rows, vocab))
+    mp.mp_softmax_xent_scaled_db(rows, vocab, zd, vocab, i32(t), st, loss2, g2, db, ws)
+    assert float(loss2) == float(loss) and np.array_equal(bits(g2), bits(g))
+    assert abs(float(loss2) - float(loss_ref)) <= 2e-6 * abs(float(loss_ref)) + 1e-6
+    # column sums of the gradient the GPU stored (its own bits), and of the oracle's gradient
+    own = L.linear_bwd(MIXED, np32(g2), np.zeros((rows, 8), np.float32), np.zeros((vocab, 8), np.float32))[2]
+    assert_close16(db, own, 1e-3, max_ulp=1, what="xent db vs sums of the stored gradient")
+    assert_close16(db, db_ref, 2e-3, max_ulp=4, what="xent db vs oracle")
+    assert mp.scale_state_read(st).found_inf == 0
+    mp.mp_softmax_xent_scaled_db(rows, vocab, zd, vocab, i32(t), st, loss2, zd, db, ws)   # in place
+    assert np.array_equal(bits(zd), bits(g))
+    with pytest.raises(mp.MPError) as e:
+        mp.mp_softmax_xent_scaled_db(rows, vocab, zd, vocab, i32(t), st, loss2, zd, db, ws_bytes(1024))
+    assert e.value.code == ML.MP_E_WORKSPACE
+
+
+def test_softmax_xent_bias_gradient_flags_overflow():
+    """Every row has the same target and a dominant logit elsewhere: the column of the dominant class sums
+    rows x S / rows = S = 2^17 > 65504, so db overflows while every stored gradient value is small."""
+    rows, vocab = 512, 32768
+    z = torch.zeros(rows, vocab, dtype=torch.float16, device="cuda")
+    z[:, 7] = 30.0
+    st = make_state(scale=2.0 ** 17)
+    loss, db = empty32(1), empty16(vocab)
+    mp.mp_softmax_xent_scaled_db(rows, vocab, z, vocab, i32(np.full(rows, 3)), st, loss, z, db,
+                                 ws_bytes(mp.mp_softmax_xent_db_workspace_bytes(rows, vocab)))
+    assert mp.scale_state_read(st).found_inf == 1
+    assert torch.isinf(db[7]) and torch.isfinite(z).all()
+
+
 def test_xent_uniform_logits_closed_form():
     rows, vocab = 8, 32768
     st = make_state(scale=2.0 ** 15)
