@@ -69,6 +69,13 @@ def test_validation_errors_enqueue_nothing():
     assert lib.mp_unscale_check_update(None, 0, C.byref(cfg), 16, 0, None) == _lib.MP_E_INVAL
     assert lib.mp_layernorm_fwd(4, 12, 16, None, 16, 16, 1e-5, 16, 16, 16, None) == _lib.MP_E_UNSUPPORTED
     assert lib.mp_mse_scaled(4, 8, 16, 16, 4, 16, 16, 16, None, 0, None) == _lib.MP_E_INVAL      # ld < cols
+    # cross-entropy with the bias gradient: shape, NULL and workspace errors come before any launch
+    assert lib.mp_softmax_xent_scaled_db(4, 8, 16, 4, 16, 16, 16, 16, 16, 16, 1 << 20, None) == _lib.MP_E_INVAL   # ld < vocab
+    assert lib.mp_softmax_xent_scaled_db(4, 8, 16, 8, 16, 16, 16, 16, None, 16, 1 << 20, None) == _lib.MP_E_INVAL  # db NULL
+    assert lib.mp_softmax_xent_scaled_db(4, 8, 16, 8, 16, 16, 16, 16, 16, 16, 8, None) == _lib.MP_E_WORKSPACE
+    assert lib.mp_softmax_xent_db_workspace_bytes(0, 8) == 0
+    assert lib.mp_softmax_xent_db_workspace_bytes(8192, 32768) >= 256 * 32768 * 4 + 8192 * 4
+    assert C.sizeof(_lib.GemmGroupItem) == C.sizeof(_lib.GemmDesc) + 4 * 8
     # grouped weight gradients: empty / oversized lists, and shapes the grouped kernel does not take
     assert lib.mp_gemm_bwd_dw_grouped(None, 0, None, None) == _lib.MP_E_INVAL
     items = (_lib.GemmGroupItem * 9)()
