@@ -703,7 +703,8 @@ def _persistent_lstm_layer(T, Bn, I, H, x_seq, w, b, dh_seq, wait_limit_us=0, ex
     return out
 
 
-@pytest.mark.parametrize("T,Bn,I,H", [(6, 8, 96, 128), (5, 20, 64, 256), (3, 32, 8, 384), (4, 1, 0, 128), (10, 32, 1024, 1024)])
+@pytest.mark.parametrize("T,Bn,I,H", [(6, 8, 96, 128), (5, 20, 64, 256), (3, 32, 8, 384), (4, 1, 0, 128), (1, 17, 8, 128),
+                                      (10, 32, 1024, 1024)])
 def test_lstm_persistent_layer_kernels(T, Bn, I, H):
     """All time steps of a layer in one launch per direction against the oracle's layer functions: every stored tensor
     of the forward pass (gate sums, h_t, fp32 cell states) and, from the GPU's own forward tensors, the gradients.
